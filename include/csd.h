@@ -1,0 +1,163 @@
+/*
+ * csd.h - C ABI of the batched verification step of Calibrated Speculative Decoding (CSD)
+ *         for AMD MI355X (gfx950).
+ *
+ * One call of csd_verify is the verification loop of Algorithm 1 for a whole batch at greedy
+ * decoding: for each of B sequences, k draft tokens are checked against k+1 rows of vocab-wide
+ * target logits.  A draft token is kept when it equals the target's argmax t*, or when it is
+ * rescued: the Online Correction Memory holds the ordered pair (draft, t*) with count >= lambda
+ * ("Candidate Proposal") AND the Semantic Consistency Gate passes, p(draft)/p(t*) >= tau on the raw
+ * logits (Eq. 3).  Every processed divergence increments its pair's count ("Dynamic Update"), rescued
+ * or not; positions after the first non-rescued divergence are neither tested nor counted.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer owned by the caller unless stated otherwise.  The library
+ *    allocates nothing, frees nothing and never synchronises: work is enqueued on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream) and results are valid once the
+ *    stream reaches that point.
+ *  - Return value: CSD_OK (0) = enqueued; a negative code = argument error detected on the host,
+ *    nothing was enqueued and no output was touched.  Conditions that only the device can see
+ *    (table full, draft id out of range) are reported through `status`.
+ *  - Batches: every memory lookup of a call reads the table as it stood when the call began; the
+ *    call's increments are applied after all lookups (kernels of one call are stream-ordered).
+ *    Calls that share a table must be ordered on one stream (or by events); concurrent calls on
+ *    one table give well-formed counts but unspecified lookup timing.
+ */
+#ifndef CSD_H
+#define CSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* return codes */
+#define CSD_OK 0
+#define CSD_EINVAL (-1)   /* bad scalar argument or NULL where a pointer is required        */
+#define CSD_EALIGN (-2)   /* logits base or row pitch not 16-byte aligned, or outputs misaligned */
+#define CSD_ENOSPACE (-3) /* workspace smaller than csd_verify_workspace_bytes()             */
+#define CSD_EHIP (-4)     /* a kernel launch was refused by the runtime                      */
+
+/* storage type of the logits */
+#define CSD_DTYPE_F32 0
+#define CSD_DTYPE_BF16 1
+
+/* csd_verify flags */
+#define CSD_APPLY_UPDATES 1u /* apply this call's count increments to the table (Algorithm 1, UpdateMemory) */
+
+/* limits */
+#define CSD_MAX_K 63           /* draft tokens per sequence                       */
+#define CSD_MAX_V (1u << 20)   /* vocabulary size (token ids fit 20 bits)         */
+
+/*
+ * Online Correction Memory: an open-addressed table of `capacity` (a power of two) 64-bit slots,
+ * linear probing, no deletion.  Slot layout (part of the ABI; a table can be copied out and decoded):
+ *     bits 63..40  count   (24 bits, saturates at CSD_OCM_COUNT_MAX)
+ *     bits 39..20  draft token id
+ *     bits 19..0   target token id (t*)
+ * The pair is ORDERED: (draft, target) as in T[(x~_i, t*)] of Algorithm 1.  An empty slot holds
+ * CSD_OCM_EMPTY (key bits all ones; no counted pair has draft == target, so it is not a valid key).
+ * An insert is dropped only when every slot is occupied by another key; the lost increments are
+ * added to status[CSD_STATUS_DROPPED].
+ */
+#define CSD_OCM_KEY_BITS 40
+#define CSD_OCM_KEY_MASK 0x000000FFFFFFFFFFull
+#define CSD_OCM_EMPTY 0x000000FFFFFFFFFFull
+#define CSD_OCM_COUNT_MAX 0xFFFFFFu
+#define CSD_OCM_KEY(draft, target) ((((uint64_t)(draft)) << 20) | (uint64_t)(target))
+
+/* status[] indices (uint32 counters, incremented by the kernels, never cleared by the library) */
+#define CSD_STATUS_DROPPED 0   /* increments lost because the table was full                     */
+#define CSD_STATUS_BAD_DRAFT 1 /* processed draft ids outside [0, V)                             */
+#define CSD_STATUS_RESCUED 2   /* positions kept by the memory + gate although draft != t*       */
+#define CSD_STATUS_COUNTED 3   /* divergences handed to UpdateMemory                             */
+#define CSD_STATUS_WORDS 4
+
+/* pos_flags bits, per draft position; 0 for positions after the stop */
+#define CSD_POS_MATCH 1u     /* draft == t*                                        */
+#define CSD_POS_FREQ 2u      /* T[(draft,t*)] >= lambda (evaluated on a divergence)  */
+#define CSD_POS_SAFE 4u      /* ratio >= tau            (evaluated on a divergence)  */
+#define CSD_POS_ACCEPTED 8u  /* position kept                                       */
+#define CSD_POS_COUNTED 16u  /* pair handed to UpdateMemory                         */
+
+/*
+ * Bytes of device scratch csd_verify needs for this shape (per-segment row partials and the
+ * step's rejection log).  Returns 0 for invalid arguments.  Host function, no GPU work.
+ */
+size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
+
+/*
+ * csd_verify - one verification step for a batch (Algorithm 1, verification loop, temperature 0;
+ * Online Correction Memory, phase 2; Semantic Consistency Gating, Eq. 3).
+ *
+ * Inputs
+ *   logits      [B][k+1][V] target logits, row-major, dtype CSD_DTYPE_F32 (float) or CSD_DTYPE_BF16
+ *               (bfloat16 bit patterns).  Row r = b*(k+1)+i starts at element r*row_stride.  Values
+ *               are finite or -inf with at least one finite value per row, |z| < 1e38; NaN/+inf are
+ *               undefined behaviour of the result (never a fault).  Base and row pitch must be
+ *               16-byte aligned.  Rows 0..k-1 of a sequence belong to its draft positions, row k is
+ *               the bonus row.
+ *   row_stride  elements between consecutive rows, >= V.
+ *   draft       [B][k] draft token ids (int32).  An id outside [0,V) is a divergence with ratio 0 that
+ *               is never rescued nor counted; status[CSD_STATUS_BAD_DRAFT] counts processed ones.
+ *               May be NULL when k == 0.
+ *   tau         gate threshold on p(draft)/p(t*) (inclusive).  tau <= 0: gate always passes;
+ *               tau > 1: never passes (strict matching).  NaN is rejected.
+ *   lambda      frequency threshold (inclusive).  0: every pair is frequent (gate-only mode).
+ *   ocm         the table, or NULL: no memory (plain strict matching, nothing is updated).
+ *   capacity    slots in `ocm`, a power of two >= 1 (ignored when ocm == NULL).
+ *   flags       CSD_APPLY_UPDATES or 0.
+ * Outputs (written for every sequence / row / position)
+ *   accept_len  [B]       n in [0,k]: draft tokens kept.
+ *   next_token  [B]       t* of the stopping position, or the argmax of the bonus row when n == k.
+ *   argmax      [B][k+1]  t* per row; ties resolve to the lowest token id (float comparison).
+ *   row_max     [B][k+1]  max logit (nullable).
+ *   row_sumexp  [B][k+1]  sum_v exp(z_v - max); p(t*) = 1/row_sumexp (nullable).
+ *   ratio       [B][k]    exp(z[draft] - max) = p(draft)/p(t*) (nullable).
+ *   p_draft     [B][k]    ratio / row_sumexp (nullable).
+ *   pos_flags   [B][k]    CSD_POS_* bits (nullable).
+ *   rej_log     [B][k]    CSD_OCM_KEY(draft, t*) for each counted divergence, CSD_OCM_EMPTY elsewhere
+ *                         (nullable; with flags == 0 it can be replayed later through csd_ocm_update).
+ *   status      [CSD_STATUS_WORDS] counters, incremented (nullable).
+ * Scratch
+ *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; contents
+ *                         are undefined afterwards.  Two calls in flight must not share a workspace.
+ * B == 0 is a valid no-op.  k == 0 verifies nothing and returns the argmax of the single row.
+ */
+int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+               uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+               int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+               uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+               void *stream);
+
+/*
+ * csd_ocm_update - add counts to the table (UpdateMemory of Algorithm 1 as a separate call; also the
+ * bulk load of a calibrated prior, Online Correction Memory phase 1).
+ *   keys     [n] CSD_OCM_KEY(draft, target); bits above the key field are ignored; entries equal to
+ *            CSD_OCM_EMPTY in the key field are skipped (so a rej_log can be passed as is).
+ *   weights  [n] increments (uint32), or NULL = 1 each.  Zero weights are skipped.
+ *   n        number of entries, 0 is a no-op.
+ * Duplicate keys are summed; counts saturate at CSD_OCM_COUNT_MAX; status as for csd_verify (nullable).
+ */
+int csd_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
+                   uint32_t *status, void *stream);
+
+/* csd_ocm_reset - set every slot to CSD_OCM_EMPTY (the empty memory an uncalibrated run starts from). */
+int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream);
+
+/*
+ * csd_ocm_lookup - read counts: counts[j] = T[keys[j]] (0 if absent).  The "Candidate Proposal" read
+ * as a stand-alone call, for inspection and tests.
+ */
+int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys, uint32_t *counts, uint64_t n,
+                   void *stream);
+
+/* Static string for a return code (host pointer, never NULL). */
+const char *csd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSD_H */

@@ -1,0 +1,217 @@
+"""ctypes binding of libcsd.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see include/csd.h) and does no
+arithmetic of the method: tensors are torch device memory, the stream is torch's current stream,
+and all work runs in the HIP kernels.  If the library has not been built the import of this
+module's functions fails loudly - there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcsd.so")
+
+CSD_OK, CSD_EINVAL, CSD_EALIGN, CSD_ENOSPACE, CSD_EHIP = 0, -1, -2, -3, -4
+CSD_DTYPE_F32, CSD_DTYPE_BF16 = 0, 1
+CSD_APPLY_UPDATES = 1
+CSD_MAX_K = 63
+CSD_MAX_V = 1 << 20
+CSD_OCM_KEY_BITS = 40
+CSD_OCM_KEY_MASK = (1 << 40) - 1
+CSD_OCM_EMPTY = (1 << 40) - 1
+CSD_OCM_COUNT_MAX = (1 << 24) - 1
+CSD_STATUS_DROPPED, CSD_STATUS_BAD_DRAFT, CSD_STATUS_RESCUED, CSD_STATUS_COUNTED = 0, 1, 2, 3
+CSD_STATUS_WORDS = 4
+CSD_POS_MATCH, CSD_POS_FREQ, CSD_POS_SAFE, CSD_POS_ACCEPTED, CSD_POS_COUNTED = 1, 2, 4, 8, 16
+
+
+class CsdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, csd_strerror(code), code))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libcsd.so (built by paper_2604_13634_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libcsd.so is not built: run `python -m paper_2604_13634_amd.build` "
+                           "(there is no CPU or PyTorch fallback for the verification path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32, u64, f32, sz = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint32,
+                                       ctypes.c_uint64, ctypes.c_float, ctypes.c_size_t)
+    lib.csd_verify_workspace_bytes.restype = sz
+    lib.csd_verify_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.csd_verify.restype = i32
+    lib.csd_verify.argtypes = [vp, i32, i64, vp, i32, i32, i32, f32, u32, vp, u64, u32,
+                               vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csd_ocm_update.restype = i32
+    lib.csd_ocm_update.argtypes = [vp, u64, vp, vp, u64, vp, vp]
+    lib.csd_ocm_reset.restype = i32
+    lib.csd_ocm_reset.argtypes = [vp, u64, vp]
+    lib.csd_ocm_lookup.restype = i32
+    lib.csd_ocm_lookup.argtypes = [vp, u64, vp, vp, u64, vp]
+    lib.csd_strerror.restype = ctypes.c_char_p
+    lib.csd_strerror.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def csd_strerror(code: int) -> str:
+    return load_library().csd_strerror(int(code)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CSD_DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return CSD_DTYPE_BF16
+    raise TypeError("logits must be float32 or bfloat16")
+
+
+def csd_verify_workspace_bytes(B: int, k: int, V: int, dtype: int) -> int:
+    return int(load_library().csd_verify_workspace_bytes(B, k, V, dtype))
+
+
+@dataclass
+class VerifyBuffers:
+    """Outputs and scratch of csd_verify for one shape, allocated once and reused across calls."""
+    B: int
+    k: int
+    V: int
+    dtype: int
+    accept_len: torch.Tensor
+    next_token: torch.Tensor
+    argmax: torch.Tensor
+    row_max: torch.Tensor
+    row_sumexp: torch.Tensor
+    ratio: torch.Tensor
+    p_draft: torch.Tensor
+    pos_flags: torch.Tensor
+    rej_log: torch.Tensor
+    status: torch.Tensor
+    workspace: torch.Tensor
+
+    @staticmethod
+    def allocate(B: int, k: int, V: int, dtype: int, device="cuda") -> "VerifyBuffers":
+        nbytes = csd_verify_workspace_bytes(B, k, V, dtype)
+        if nbytes == 0:
+            raise CsdError(CSD_EINVAL, "csd_verify_workspace_bytes")
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        return VerifyBuffers(
+            B, k, V, dtype,
+            accept_len=e((B,), torch.int32), next_token=e((B,), torch.int32), argmax=e((B, k + 1), torch.int32),
+            row_max=e((B, k + 1), torch.float32), row_sumexp=e((B, k + 1), torch.float32),
+            ratio=e((B, k), torch.float32), p_draft=e((B, k), torch.float32), pos_flags=e((B, k), torch.uint8),
+            rej_log=e((B, k), torch.int64), status=torch.zeros((CSD_STATUS_WORDS,), dtype=torch.int32, device=device),
+            workspace=e((nbytes,), torch.uint8))
+
+
+def new_ocm(capacity: int, device="cuda") -> torch.Tensor:
+    """An empty Online Correction Memory: int64 tensor of `capacity` slots, reset on the current stream."""
+    ocm = torch.empty((capacity,), dtype=torch.int64, device=device)
+    csd_ocm_reset(ocm)
+    return ocm
+
+
+def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
+               ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+               buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True) -> VerifyBuffers:
+    """Enqueue one verification step.  logits: [B][k+1][V] (float32 or bfloat16), draft: [B][k] int32.
+
+    Returns the VerifyBuffers holding the outputs (valid once the stream has run the call).
+    With diagnostics=False the optional outputs (row_max ... rej_log) are not written."""
+    if logits.dim() != 3:
+        raise ValueError("logits must be [B][k+1][V]")
+    B, K1, V = logits.shape
+    k = K1 - 1
+    if logits.stride(2) != 1 or (B > 1 and logits.stride(0) != K1 * logits.stride(1)):
+        raise ValueError("logits rows must be equally spaced with unit element stride")
+    row_stride = logits.stride(1) if K1 > 1 or B > 1 else max(V, logits.stride(1))
+    if draft is not None:
+        if draft.dtype != torch.int32 or tuple(draft.shape) != (B, k) or not draft.is_contiguous():
+            raise ValueError("draft must be a contiguous int32 [B][k] tensor")
+    dt = _dtype_code(logits)
+    if buffers is None:
+        buffers = VerifyBuffers.allocate(B, k, V, dt, logits.device)
+    elif (buffers.B, buffers.k, buffers.V, buffers.dtype) != (B, k, V, dt):
+        raise ValueError("buffers were allocated for another shape")
+    if ocm is not None and (ocm.dtype != torch.int64 or not ocm.is_contiguous()):
+        raise ValueError("ocm must be a contiguous int64 tensor")
+    bf = buffers
+    opt = (lambda t: _ptr(t)) if diagnostics else (lambda t: None)
+    rc = load_library().csd_verify(
+        _ptr(logits), dt, row_stride, _ptr(draft), B, k, V, float(tau), int(lam) & 0xFFFFFFFF,
+        _ptr(ocm), 0 if ocm is None else ocm.numel(), int(flags),
+        _ptr(bf.accept_len), _ptr(bf.next_token), _ptr(bf.argmax), opt(bf.row_max), opt(bf.row_sumexp),
+        opt(bf.ratio), opt(bf.p_draft), opt(bf.pos_flags), opt(bf.rej_log), _ptr(bf.status),
+        _ptr(bf.workspace), bf.workspace.numel(), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_verify")
+    return bf
+
+
+def csd_ocm_update(ocm: torch.Tensor, keys: torch.Tensor, weights: Optional[torch.Tensor] = None,
+                   status: Optional[torch.Tensor] = None, stream=None) -> None:
+    """T[key] += weight for every entry (keys: int64 CSD_OCM_KEY values; weights: int32 or None = 1)."""
+    if keys.dtype != torch.int64 or not keys.is_contiguous():
+        raise ValueError("keys must be contiguous int64")
+    if weights is not None and (weights.dtype != torch.int32 or weights.numel() != keys.numel()
+                                or not weights.is_contiguous()):
+        raise ValueError("weights must be contiguous int32, one per key")
+    rc = load_library().csd_ocm_update(_ptr(ocm), ocm.numel(), _ptr(keys), _ptr(weights), keys.numel(), _ptr(status),
+                                       _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_ocm_update")
+
+
+def csd_ocm_reset(ocm: torch.Tensor, stream=None) -> None:
+    rc = load_library().csd_ocm_reset(_ptr(ocm), ocm.numel(), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_ocm_reset")
+
+
+def csd_ocm_lookup(ocm: torch.Tensor, keys: torch.Tensor, stream=None) -> torch.Tensor:
+    counts = torch.empty((keys.numel(),), dtype=torch.int32, device=keys.device)
+    rc = load_library().csd_ocm_lookup(_ptr(ocm), ocm.numel(), _ptr(keys), _ptr(counts), keys.numel(), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_ocm_lookup")
+    return counts
+
+
+def decode_ocm(ocm: torch.Tensor) -> Dict[Tuple[int, int], int]:
+    """Copy a table to the host and unpack its slots into {(draft, target): count} (layout of csd.h)."""
+    import numpy as np
+    raw = ocm.detach().cpu().numpy().view(np.uint64)
+    key = raw & np.uint64(CSD_OCM_KEY_MASK)
+    used = key != np.uint64(CSD_OCM_EMPTY)
+    key = key[used]
+    cnt = (raw[used] >> np.uint64(CSD_OCM_KEY_BITS)).astype(np.int64)
+    d = (key >> np.uint64(20)).astype(np.int64)
+    t = (key & np.uint64((1 << 20) - 1)).astype(np.int64)
+    out: Dict[Tuple[int, int], int] = {}
+    for a, b, c in zip(d.tolist(), t.tolist(), cnt.tolist()):
+        assert (a, b) not in out, "a key occupies two slots"
+        out[(a, b)] = c
+    return out

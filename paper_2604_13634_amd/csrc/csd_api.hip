@@ -1,0 +1,148 @@
+// C ABI of the CSD verification library: argument validation and kernel sequencing.
+// Nothing here allocates, frees or synchronises; every entry point only enqueues on the caller's stream.
+#include <cstring>
+
+#include "csd_internal.h"
+
+namespace csd {
+
+WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
+    WorkspaceLayout w;
+    w.partials_off = 0;
+    w.partials_bytes = (size_t)p.rows * (size_t)p.partials_per_row * sizeof(RowPartial);
+    w.log_off = (w.partials_off + w.partials_bytes + 255) & ~(size_t)255;
+    w.log_bytes = (size_t)B * (size_t)k * sizeof(uint64_t);
+    w.total = ((w.log_off + w.log_bytes + 255) & ~(size_t)255) + 256;   // never 0, so a valid shape is told from an invalid one
+    return w;
+}
+
+namespace {
+
+bool shape_ok(int B, int k, int V, int dtype) {
+    if (B < 0 || k < 0 || k > CSD_MAX_K) return false;
+    if (V < 1 || (uint32_t)V > CSD_MAX_V) return false;
+    if (dtype != CSD_DTYPE_F32 && dtype != CSD_DTYPE_BF16) return false;
+    if ((int64_t)B * (k + 1) > (int64_t)1 << 24) return false;   // keeps every grid and index within 31 bits
+    return true;
+}
+
+bool is_nan_bits(float f) {   // bit test: independent of the floating-point options of the build
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    return (u & 0x7FFFFFFFu) > 0x7F800000u;
+}
+bool is_pow2(uint64_t x) { return x != 0 && (x & (x - 1)) == 0; }
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+}  // namespace
+}  // namespace csd
+
+using namespace csd;
+
+extern "C" {
+
+size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype) {
+    if (!shape_ok(B, k, V, dtype)) return 0;
+    const StreamPlan p = make_stream_plan(B, k, V, dtype);
+    return make_workspace_layout(p, B, k).total;
+}
+
+int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+               uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+               int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+               uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+               void *stream) {
+    if (!shape_ok(B, k, V, dtype)) return CSD_EINVAL;
+    if (is_nan_bits(tau)) return CSD_EINVAL;
+    if (flags & ~CSD_APPLY_UPDATES) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    if (!logits || !accept_len || !next_token || !argmax || !workspace) return CSD_EINVAL;
+    if (k > 0 && !draft) return CSD_EINVAL;
+    if (row_stride < V) return CSD_EINVAL;
+    if (ocm && !is_pow2(capacity)) return CSD_EINVAL;
+    const size_t esz = (dtype == CSD_DTYPE_F32) ? 4 : 2;
+    if (!aligned(logits, 16) || ((size_t)row_stride * esz) % 16 != 0) return CSD_EALIGN;
+    if (!aligned(workspace, 16) || !aligned(accept_len, 4) || !aligned(next_token, 4) || !aligned(argmax, 4) ||
+        !aligned(draft, 4) || !aligned(row_max, 4) || !aligned(row_sumexp, 4) || !aligned(ratio, 4) ||
+        !aligned(p_draft, 4) || !aligned(rej_log, 8) || !aligned(ocm, 8) || !aligned(status, 4))
+        return CSD_EALIGN;
+
+    const StreamPlan plan = make_stream_plan(B, k, V, dtype);
+    const WorkspaceLayout ws = make_workspace_layout(plan, B, k);
+    if (workspace_bytes < ws.total) return CSD_ENOSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    RowPartial *partials = (RowPartial *)((char *)workspace + ws.partials_off);
+    const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
+    uint64_t *log = rej_log ? rej_log : (apply ? (uint64_t *)((char *)workspace + ws.log_off) : nullptr);
+
+    if (launch_row_stream(logits, dtype, row_stride, V, plan, partials, st) != hipSuccess) return CSD_EHIP;
+
+    EpilogueArgs a;
+    a.logits = logits;
+    a.dtype = dtype;
+    a.row_stride = row_stride;
+    a.draft = draft;
+    a.B = B;
+    a.k = k;
+    a.V = V;
+    a.tau = tau;
+    a.lambda = lambda;
+    a.ocm = ocm;
+    a.capacity = capacity;
+    a.partials = partials;
+    a.partials_per_row = plan.partials_per_row;
+    a.accept_len = accept_len;
+    a.next_token = next_token;
+    a.argmax = argmax;
+    a.row_max = row_max;
+    a.row_sumexp = row_sumexp;
+    a.ratio = ratio;
+    a.p_draft = p_draft;
+    a.pos_flags = pos_flags;
+    a.rej_log = log;
+    a.status = status;
+    if (launch_epilogue(a, st) != hipSuccess) return CSD_EHIP;
+
+    if (apply) {
+        if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
+    }
+    return CSD_OK;
+}
+
+int csd_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
+                   uint32_t *status, void *stream) {
+    if (!ocm || !is_pow2(capacity)) return CSD_EINVAL;
+    if (n == 0) return CSD_OK;
+    if (!keys || n > ((uint64_t)1 << 40)) return CSD_EINVAL;
+    if (!aligned(ocm, 8) || !aligned(keys, 8) || !aligned(weights, 4) || !aligned(status, 4)) return CSD_EALIGN;
+    return launch_ocm_update(ocm, capacity, keys, weights, n, status, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream) {
+    if (!ocm || !is_pow2(capacity)) return CSD_EINVAL;
+    if (!aligned(ocm, 8)) return CSD_EALIGN;
+    return launch_ocm_reset(ocm, capacity, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys, uint32_t *counts, uint64_t n,
+                   void *stream) {
+    if (!ocm || !is_pow2(capacity)) return CSD_EINVAL;
+    if (n == 0) return CSD_OK;
+    if (!keys || !counts) return CSD_EINVAL;
+    if (!aligned(ocm, 8) || !aligned(keys, 8) || !aligned(counts, 4)) return CSD_EALIGN;
+    return launch_ocm_lookup(ocm, capacity, keys, counts, n, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+const char *csd_strerror(int code) {
+    switch (code) {
+        case CSD_OK: return "ok";
+        case CSD_EINVAL: return "invalid argument";
+        case CSD_EALIGN: return "misaligned pointer or row pitch";
+        case CSD_ENOSPACE: return "workspace too small";
+        case CSD_EHIP: return "kernel launch failed";
+        default: return "unknown csd error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every entry point the
+header declares, and rejects bad arguments before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2604_13634_amd", "libcsd.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libcsd.so not built (run __graft_entry__.build())")
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "csd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(csd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_entry_point_is_exported():
+    lib = ctypes.CDLL(LIB)
+    names = _declared_functions()
+    assert {"csd_verify", "csd_ocm_update", "csd_ocm_reset", "csd_verify_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_exposes_the_same_names():
+    from paper_2604_13634_amd import binding
+    for n in _declared_functions():
+        assert callable(getattr(binding, n)), n
+
+
+def test_header_constants_match_binding():
+    from paper_2604_13634_amd import binding
+    text = open(os.path.join(ROOT, "include", "csd.h")).read()
+    for name, val in re.findall(r"#define\s+(CSD_[A-Z_0-9]+)\s+\(?(-?\d+)u?\)?\s*(?:/\*.*)?\n", text):
+        if hasattr(binding, name):
+            assert getattr(binding, name) == int(val), name
+    assert binding.CSD_OCM_EMPTY == 0xFFFFFFFFFF and binding.CSD_OCM_COUNT_MAX == 0xFFFFFF
+
+
+def test_workspace_query_is_pure_host_arithmetic():
+    from paper_2604_13634_amd import binding as b
+    assert b.csd_verify_workspace_bytes(1, 4, 32000, b.CSD_DTYPE_F32) > 0
+    big = b.csd_verify_workspace_bytes(256, 4, 256000, b.CSD_DTYPE_BF16)
+    assert 0 < big < (1 << 22)
+    assert b.csd_verify_workspace_bytes(0, 4, 100, 0) > 0
+    for bad in [(-1, 4, 100, 0), (1, -1, 100, 0), (1, 64, 100, 0), (1, 4, 0, 0), (1, 4, (1 << 20) + 1, 0), (1, 4, 100, 2)]:
+        assert b.csd_verify_workspace_bytes(*bad) == 0
+
+
+def test_argument_errors_are_synchronous_and_enqueue_nothing():
+    """Every call below fails validation on the host, so no pointer is ever dereferenced."""
+    from paper_2604_13634_amd import binding as b
+    lib = b.load_library()
+    P = ctypes.c_void_p
+    good = 0x10000                       # a fake, aligned, never-used address
+    ws = b.csd_verify_workspace_bytes(2, 3, 1000, 0)
+
+    def verify(logits=good, dtype=0, stride=1000, draft=good, B=2, k=3, V=1000, tau=0.3, lam=2, ocm=None, cap=0,
+               flags=0, acc=good, nxt=good, am=good, work=good, wsz=ws):
+        return lib.csd_verify(P(logits), dtype, stride, P(draft), B, k, V, tau, lam, P(ocm), cap, flags, P(acc), P(nxt),
+                              P(am), None, None, None, None, None, None, None, P(work), wsz, None)
+
+    assert verify(B=-1) == b.CSD_EINVAL
+    assert verify(k=64) == b.CSD_EINVAL
+    assert verify(V=0) == b.CSD_EINVAL
+    assert verify(V=(1 << 20) + 1, stride=1 << 21) == b.CSD_EINVAL
+    assert verify(dtype=3) == b.CSD_EINVAL
+    assert verify(tau=float("nan")) == b.CSD_EINVAL
+    assert verify(flags=2) == b.CSD_EINVAL
+    assert verify(logits=None) == b.CSD_EINVAL
+    assert verify(draft=None) == b.CSD_EINVAL
+    assert verify(acc=None) == b.CSD_EINVAL
+    assert verify(work=None) == b.CSD_EINVAL
+    assert verify(stride=999) == b.CSD_EINVAL
+    assert verify(ocm=good, cap=1000) == b.CSD_EINVAL          # capacity must be a power of two
+    assert verify(ocm=good, cap=0) == b.CSD_EINVAL
+    assert verify(logits=good + 4) == b.CSD_EALIGN
+    assert verify(stride=1001) == b.CSD_EALIGN                 # 4004-byte pitch
+    assert verify(dtype=1, stride=1004) == b.CSD_EALIGN        # bf16: 2008-byte pitch
+    assert verify(am=good + 2) == b.CSD_EALIGN
+    assert verify(ocm=good + 4, cap=1024) == b.CSD_EALIGN
+    assert verify(wsz=ws - 1) == b.CSD_ENOSPACE
+    assert verify(B=0, logits=None, draft=None, acc=None, nxt=None, am=None, work=None, wsz=0) == b.CSD_OK
+
+    assert lib.csd_ocm_reset(None, 1024, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_reset(P(good), 1000, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_update(P(good), 1024, None, None, 5, None, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_update(P(good), 1024, None, None, 0, None, None) == b.CSD_OK
+    assert lib.csd_ocm_update(P(good), 1024, P(good + 1), None, 5, None, None) == b.CSD_EALIGN
+    assert lib.csd_ocm_lookup(P(good), 1024, P(good), None, 5, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_lookup(P(good), 3, P(good), P(good), 5, None) == b.CSD_EINVAL
+    assert b.csd_strerror(b.CSD_ENOSPACE) == "workspace too small"

@@ -1,0 +1,323 @@
+"""GPU parity: csd_verify / csd_ocm_* through the C ABI against the fp64 oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from gen import CONFIGS, Workload, f32_to_bf16_bits
+from oracle import csd_oracle as O
+from paper_2604_13634_amd import binding as csd
+from parity_util import compare_step, compare_table, run_stream, to_device_logits
+
+pytestmark = pytest.mark.gpu
+
+
+def _prior_from_pairs(w, lam, n=64):
+    """A calibrated prior: the head of the divergence-pair map, already at the frequency threshold."""
+    pairs = [(int(d), int(t)) for t, d in zip(w.pair_target[:n], w.pair_draft[:n])]
+    return pairs, [lam] * len(pairs)
+
+
+# --------------------------------------------------------------------------- streams with an evolving memory
+def test_config0_full_stream():
+    """Config 0 exactly: B=1, k=4, V=32000, fp32, 1000 steps, empty memory at start."""
+    w = Workload(CONFIGS[0])
+    orc, ocm, rescued, counted = run_stream(w, range(w.cfg.steps), check_table_every=100)
+    assert rescued > 20 and counted > 500
+
+
+@pytest.mark.parametrize("ci,V,steps", [(1, 4099, 400), (2, 8200, 150), (3, 3001, 100), (4, 2048 + 6, 120)])
+def test_long_streams_reduced_vocab(ci, V, steps):
+    """Configs 1-4 with their batch, k, tau, lambda, pair skew and storage type over many steps,
+    on a reduced ragged vocabulary so that the oracle keeps up; the memory evolves from empty."""
+    cfg = CONFIGS[ci]
+    w = Workload(cfg, V=V, n_pairs=min(cfg.n_pairs, 1024))
+    orc, ocm, rescued, counted = run_stream(w, range(steps), check_table_every=25)
+    assert rescued > 0 and counted > steps
+
+
+@pytest.mark.parametrize("ci,steps", [(1, 6), (2, 3), (3, 2), (4, 2)])
+def test_full_size_steps_with_prior(ci, steps):
+    """Configs 1-4 at full size (the shapes bench.py times) for a few steps, memory pre-loaded with a
+    prior so that rescues happen from the first step."""
+    w = Workload(CONFIGS[ci])
+    prior = _prior_from_pairs(w, w.cfg.lam, n=min(512, w.cfg.n_pairs))
+    orc, ocm, rescued, counted = run_stream(w, range(steps), prior=prior, check_table_every=1, threads=16)
+    assert rescued > 0
+
+
+# --------------------------------------------------------------------------- row statistics: shapes, ties, ranges
+def _verify_rows(z_np, draft_np=None, tau=0.3, lam=2, ocm=None, flags=0):
+    B, K1, V = z_np.shape
+    if draft_np is None:
+        draft_np = np.zeros((B, K1 - 1), dtype=np.int32)
+    zt = to_device_logits(z_np)
+    bf = csd.csd_verify(zt, torch.from_numpy(draft_np).cuda(), tau, lam, ocm, flags)
+    torch.cuda.synchronize()
+    return bf
+
+
+def _check_against_oracle(z_np, draft_np=None, tau=0.3, lam=2):
+    B, K1, V = z_np.shape
+    if draft_np is None:
+        draft_np = np.zeros((B, K1 - 1), dtype=np.int32)
+    bf = _verify_rows(z_np, draft_np, tau, lam)
+    res = O.CSDOracle().verify_step(np.ascontiguousarray(z_np), draft_np, tau=np.float32(tau), lam=lam, use_ocm=False)
+    compare_step(res, bf, "V=%d" % V)
+    return bf, res
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 255, 1023, 1024, 1025, 4095, 4097, 8191, 8193,
+                               16385, 40000, 70001])
+def test_ragged_vocab_sizes(dtype, V):
+    rng = np.random.default_rng(V)
+    z = (rng.standard_normal((3, 3, V)) * 3).astype(np.float32)
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z).reshape(3, 3, V)
+    draft = rng.integers(0, V, size=(3, 2)).astype(np.int32)
+    _check_against_oracle(z, draft)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_row_stride_larger_than_vocab(dtype):
+    rng = np.random.default_rng(7)
+    V, pitch = 3000, 3016
+    zp = (rng.standard_normal((2, 4, pitch)) * 3).astype(np.float32)
+    zp[..., V:] = 100.0                       # padding must never be read as logits
+    if dtype == "bf16":
+        zp = f32_to_bf16_bits(zp).reshape(2, 4, pitch)
+    draft = rng.integers(0, V, size=(2, 3)).astype(np.int32)
+    zt = to_device_logits(zp)[..., :V]
+    bf = csd.csd_verify(zt, torch.from_numpy(draft).cuda(), 0.3, 2, None, 0)
+    torch.cuda.synchronize()
+    res = O.CSDOracle().verify_step(np.ascontiguousarray(zp[..., :V]), draft, tau=np.float32(0.3), lam=2, use_ocm=False)
+    compare_step(res, bf, "strided")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ties_resolve_to_lowest_id_everywhere(dtype):
+    """Equal maxima inside one 16-byte chunk, across lanes, waves, tiles and row segments."""
+    V = 150000
+    rng = np.random.default_rng(3)
+    spots = [(0, 1), (5, 6), (3, 64 * 8 + 3), (1000, 1001), (2047, 2048), (4095, 4096), (8191, 8192), (100, 140000),
+             (70000, 70001), (V - 2, V - 1), (65535, 65536), (32767, 98304)]
+    z = (rng.standard_normal((len(spots), 2, V))).astype(np.float32)
+    for r, (a, b) in enumerate(spots):
+        z[r, 0, a] = 9.0
+        z[r, 0, b] = 9.0
+        z[r, 1, b] = 9.0
+        z[r, 1, a] = 9.0 if r % 2 else 8.5
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z).reshape(z.shape)
+    bf, res = _check_against_oracle(z)
+    assert [int(x) for x in bf.argmax[:, 0].cpu()] == [a for a, _ in spots]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_constant_rows_and_signed_zero(dtype):
+    V = 20000
+    z = np.full((2, 2, V), 1.5, dtype=np.float32)
+    z[1, 0, :] = -0.0
+    z[1, 0, 77] = 0.0
+    z[1, 1, :] = -3.0
+    z[1, 1, 5000] = -0.0
+    z[1, 1, 9000] = 0.0
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z).reshape(z.shape)
+    bf, res = _check_against_oracle(z)
+    assert bf.argmax.cpu().tolist() == [[0, 0], [0, 5000]]
+    assert float(bf.row_sumexp[0, 0]) == pytest.approx(V, rel=1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_masked_vocab_and_extreme_ranges(dtype):
+    """-inf entries, maxima that climb steeply along the row (reference rescaling), huge and tiny magnitudes."""
+    V = 50000
+    rng = np.random.default_rng(9)
+    z = (rng.standard_normal((1, 8, V)) * 2).astype(np.float32)
+    z[0, 0, rng.random(V) < 0.7] = -np.inf                       # mostly masked
+    z[0, 1, :] = -np.inf
+    z[0, 1, 43210] = -5.0                                        # a single finite value, late in the row
+    z[0, 2, :] = np.linspace(-300.0, 300.0, V)                   # ascending ramp: many rescales
+    z[0, 3, :] = np.linspace(300.0, -300.0, V)                   # descending ramp
+    z[0, 4, :] *= 1000.0                                         # spread of thousands
+    z[0, 5, :] = z[0, 5, :] * 1e-3 + 1e4                         # large offset, tiny spread
+    z[0, 6, :] = -1e30
+    z[0, 6, 123] = -9.9e29
+    z[0, 7, : V // 2] = -np.inf                                  # first segments hold nothing finite
+    if dtype == "bf16":
+        fin = np.isfinite(z)
+        zb = np.where(fin, z, 0).astype(np.float32)
+        bits = f32_to_bf16_bits(zb).reshape(z.shape)
+        bits[~fin] = 0xFF80
+        z = bits
+    draft = np.array([[1, 43210, V - 1, 0, 17, 99, 123]], dtype=np.int32)
+    _check_against_oracle(z, draft)
+
+
+def test_many_rows_and_k_limits():
+    rng = np.random.default_rng(21)
+    for B, k, V in [(1, 0, 5000), (3, 63, 700), (700, 1, 300), (33, 15, 2500)]:
+        z = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+        draft = rng.integers(0, V, size=(B, k)).astype(np.int32)
+        am = z[:, :k].argmax(axis=-1)
+        draft = np.where(rng.random((B, k)) < 0.8, am, draft).astype(np.int32)
+        bf = _verify_rows(z, draft, tau=0.2, lam=0, ocm=csd.new_ocm(1 << 12), flags=0)
+        res = O.CSDOracle().verify_step(z, draft, tau=np.float32(0.2), lam=0, apply_updates=False)
+        compare_step(res, bf, "B=%d k=%d" % (B, k))
+    # an empty batch is a no-op that must not fail
+    zt = torch.empty((0, 3, 100), dtype=torch.float32, device="cuda")
+    rc = csd.load_library().csd_verify(None, 0, 100, None, 0, 2, 100, 0.3, 2, None, 0, 0, None, None, None, None, None,
+                                       None, None, None, None, None, None, 0, None)
+    assert rc == csd.CSD_OK
+
+
+# --------------------------------------------------------------------------- gate / memory modes
+def test_modes_strict_gate_only_memory_only():
+    """No memory = strict matching; lambda = 0 = gate only; tau <= 0 = memory only; tau > 1 = strict."""
+    w = Workload(CONFIGS[2], V=3000, B=16)
+    cfg = w.cfg
+    prior = _prior_from_pairs(w, 5, n=256)
+    for tau, lam, use_ocm in [(0.25, 3, False), (0.6, 0, True), (0.0, 3, True), (-1.0, 3, True), (1.0001, 0, True),
+                              (1.0, 0, True), (0.25, 2 ** 32 - 1, True)]:
+        orc = O.CSDOracle()
+        orc.ocm_update(*prior)
+        ocm = csd.new_ocm(4096)
+        csd.csd_ocm_update(ocm, torch.tensor([(d << 20) | t for d, t in prior[0]], dtype=torch.int64, device="cuda"),
+                           torch.tensor(prior[1], dtype=torch.int32, device="cuda"))
+        for step in range(6):
+            z, draft = w.step(step)
+            bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), tau, lam, ocm if use_ocm else None)
+            torch.cuda.synchronize()
+            res = orc.verify_step(z, draft, tau=np.float32(tau), lam=lam, use_ocm=use_ocm)
+            compare_step(res, bf, "tau=%g lam=%d ocm=%s step %d" % (tau, lam, use_ocm, step))
+        compare_table(ocm, orc)
+
+
+def test_deferred_updates_through_rejection_log():
+    """flags = 0 leaves the memory untouched; replaying rej_log through csd_ocm_update gives the fused result."""
+    w = Workload(CONFIGS[4], V=2048, B=64)
+    cfg = w.cfg
+    ocm_a, ocm_b = csd.new_ocm(1 << 14), csd.new_ocm(1 << 14)
+    orc = O.CSDOracle()
+    for step in range(30):
+        z, draft = w.step(step)
+        zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+        bfa = csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm_a, csd.CSD_APPLY_UPDATES)
+        before = ocm_b.clone()
+        bfb = csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm_b, 0)
+        torch.cuda.synchronize()
+        assert torch.equal(before, ocm_b)
+        csd.csd_ocm_update(ocm_b, bfb.rej_log.view(-1))
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=cfg.lam)
+        compare_step(res, bfa, "fused step %d" % step)
+        compare_step(res, bfb, "deferred step %d" % step)
+    compare_table(ocm_a, orc)
+    compare_table(ocm_b, orc)
+
+
+def test_bad_draft_ids_are_divergences_never_counted():
+    rng = np.random.default_rng(4)
+    B, k, V = 8, 4, 1000
+    z = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+    am = z[:, :k].argmax(axis=-1).astype(np.int32)
+    draft = am.copy()
+    draft[0, 1] = V
+    draft[1, 0] = -1
+    draft[2, 3] = 2 ** 31 - 1
+    draft[3, 2] = -2 ** 31
+    draft[4, 0] = (am[4, 0] + 1) % V          # ordinary divergence first: the bad id behind it is not processed
+    draft[4, 1] = V + 5
+    # tau = 0: the ordinary divergence of sequence 4 is rescued, so the bad id behind it is reached (5 in all);
+    # tau = 0.999: it is not rescued and the scan stops before the bad id (4 in all)
+    for tau, n_bad in [(0.0, 5), (0.999, 4)]:
+        ocm = csd.new_ocm(256)
+        orc = O.CSDOracle()
+        bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), tau, 0, ocm)
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, draft, tau=np.float32(tau), lam=0)
+        compare_step(res, bf, "bad ids")
+        compare_table(ocm, orc)
+        assert int(bf.status[csd.CSD_STATUS_BAD_DRAFT]) == orc.bad_draft == n_bad
+
+
+# --------------------------------------------------------------------------- the memory on its own
+def test_ocm_update_duplicates_weights_lookup():
+    rng = np.random.default_rng(5)
+    n = 200000
+    d = rng.zipf(1.3, size=n) % 5000
+    t = (d + 1 + rng.integers(0, 50, size=n)) % 5000
+    keep = d != t
+    d, t = d[keep], t[keep]
+    wts = rng.integers(0, 4, size=d.size).astype(np.int32)          # zeros are skipped
+    ocm = csd.new_ocm(1 << 16)
+    orc = O.CSDOracle(capacity=1 << 16)
+    keys = torch.from_numpy(((d.astype(np.int64) << 20) | t.astype(np.int64))).cuda()
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    csd.csd_ocm_update(ocm, keys, torch.from_numpy(wts).cuda(), status)
+    csd.csd_ocm_update(ocm, keys[:1000], None, status)
+    orc.ocm_update(zip(d.tolist(), t.tolist()), wts.tolist())
+    orc.ocm_update(zip(d[:1000].tolist(), t[:1000].tolist()))
+    compare_table(ocm, orc)
+    assert int(status[0]) == 0
+    q = torch.cat([keys[:500], torch.tensor([(7 << 20) | 7, csd.CSD_OCM_EMPTY, (4999 << 20) | 4998], dtype=torch.int64,
+                                            device="cuda")])
+    got = csd.csd_ocm_lookup(ocm, q).cpu().tolist()
+    want = [orc.T.get((int(x) >> 20, int(x) & 0xFFFFF), 0) for x in q.cpu().tolist()]
+    want[-2] = 0
+    assert got == want
+
+
+def test_ocm_hot_key_contention_and_saturation():
+    """Hundreds of thousands of increments onto a handful of keys; then saturation at 2^24 - 1."""
+    n = 1 << 20
+    rng = np.random.default_rng(6)
+    d = rng.integers(0, 4, size=n)
+    t = d + 10
+    keys = torch.from_numpy((d.astype(np.int64) << 20) | t.astype(np.int64)).cuda()
+    ocm = csd.new_ocm(64)
+    csd.csd_ocm_update(ocm, keys)
+    got = csd.decode_ocm(ocm)
+    assert got == {(i, i + 10): int((d == i).sum()) for i in range(4)}
+    big = torch.full((40,), 2 ** 31 - 1, dtype=torch.int32, device="cuda")
+    csd.csd_ocm_update(ocm, keys[:40], big)
+    got = csd.decode_ocm(ocm)
+    assert all(got[(int(a), int(a) + 10)] == csd.CSD_OCM_COUNT_MAX for a in set(d[:40].tolist()))
+    csd.csd_ocm_update(ocm, keys[:40])
+    assert csd.decode_ocm(ocm) == got
+
+
+def test_ocm_full_table_drops_are_reported():
+    ocm = csd.new_ocm(8)
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    orc = O.CSDOracle(capacity=8)
+    for j in range(12):                      # one new key per call: which insert is dropped is then well defined
+        key = torch.tensor([((j + 1) << 20) | (j + 100)], dtype=torch.int64, device="cuda")
+        wt = torch.tensor([j + 1], dtype=torch.int32, device="cuda")
+        csd.csd_ocm_update(ocm, key, wt, status)
+        orc.ocm_update([(j + 1, j + 100)], [j + 1])
+    compare_table(ocm, orc)
+    assert int(status[csd.CSD_STATUS_DROPPED]) == orc.dropped == 9 + 10 + 11 + 12
+    # existing keys are still updated and found in a full table; absent keys read 0
+    keys = torch.tensor([(3 << 20) | 102, (12 << 20) | 111], dtype=torch.int64, device="cuda")
+    csd.csd_ocm_update(ocm, keys[:1], None, status)
+    assert csd.csd_ocm_lookup(ocm, keys).cpu().tolist() == [4, 0]
+    csd.csd_ocm_reset(ocm)
+    assert csd.decode_ocm(ocm) == {}
+
+
+def test_verify_on_a_side_stream():
+    w = Workload(CONFIGS[1], V=5000)
+    cfg = w.cfg
+    z, draft = w.step(0)
+    s = torch.cuda.Stream()
+    zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        ocm = csd.new_ocm(1 << 12)
+        bf = csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm)
+    s.synchronize()
+    orc = O.CSDOracle()
+    compare_step(orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=cfg.lam), bf, "side stream")
+    compare_table(ocm, orc)
