@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSD verification hot path on one MI355X.
+
+A step is one csd_verify call on one batch: the streaming pass over all B*(k+1) logit rows, the
+per-sequence epilogue (draft probability, memory lookup, gate, accepted-prefix scan) and the
+memory updates.  Logits are synthetic (seeded generator, see gen/), already resident in HBM, and
+replayed from a ring of distinct steps larger than the last-level cache (>= 1 GiB, >= 4 steps) so
+that every step's rows come from HBM.
+
+Prints ONE JSON line: whole-path throughput in verified positions (rows) per second, the
+verify kernel's achieved HBM bandwidth against the 8 TB/s peak (timed live with events on the
+launch stream over the timed region; one launch per step), and the CPU oracle's rate on the host cores.
+"""
+import argparse
+import hashlib
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak, GB/s
+
+
+def kernel_fingerprint() -> str:
+    """Hash of the row-stream kernel's source and build flags: stored counter readings apply to one version only."""
+    h = hashlib.sha256()
+    for rel in ("paper_2604_13634_amd/csrc/csd_verify.hip", "paper_2604_13634_amd/csrc/csd_device.h",
+                "paper_2604_13634_amd/csrc/csd_internal.h", "paper_2604_13634_amd/build.py"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload index 0..4 (default: the largest, 4)")
+    ap.add_argument("--ring-bytes", type=float, default=float(1 << 30), help="minimum bytes of distinct logits in the ring")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gen-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from gen import CONFIGS, Workload
+    from paper_2604_13634_amd import binding as csd
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity_util import to_device_logits
+
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.config]
+    w = Workload(cfg)
+    rows = cfg.rows
+    n_ring = max(4, int(math.ceil(args.ring_bytes / cfg.bytes_per_step)))
+
+    # ---- inputs: generated on the host, copied to HBM before anything is timed
+    t_gen = time.perf_counter()
+    ring_host, ring_z, ring_d = [], [], []
+    for s in range(n_ring):
+        z, d = w.step(s, threads=args.gen_threads)
+        ring_z.append(to_device_logits(z))
+        ring_d.append(torch.from_numpy(d).cuda())
+        if s < 4:
+            ring_host.append((z, d))
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    dt = csd.CSD_DTYPE_F32 if cfg.dtype == "f32" else csd.CSD_DTYPE_BF16
+    bf = csd.VerifyBuffers.allocate(cfg.B, cfg.k, cfg.V, dt)
+
+    def timed_steps(flags, steps, warmup):
+        ocm = csd.new_ocm(cfg.capacity)
+        for i in range(warmup):
+            csd.csd_verify(ring_z[i % n_ring], ring_d[i % n_ring], cfg.tau, cfg.lam, ocm, flags, buffers=bf)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()                                   # events on the stream the kernels are launched on
+        for i in range(steps):
+            j = (warmup + i) % n_ring
+            csd.csd_verify(ring_z[j], ring_d[j], cfg.tau, cfg.lam, ocm, flags, buffers=bf)
+        e1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ocm, e0.elapsed_time(e1) / steps
+
+    # ---- the headline: whole hot path (one kernel launch per step), memory updates applied
+    elapsed, ocm, fused_ms = timed_steps(csd.CSD_APPLY_UPDATES, args.steps, args.warmup)
+    ms_per_step = elapsed / args.steps * 1e3
+    value = rows * args.steps / elapsed
+    accept_rate = float(bf.accept_len.float().mean().item()) / max(cfg.k, 1)
+    status = bf.status.cpu().numpy().view(np.uint32).tolist()
+    elapsed_noupd, _, _ = timed_steps(0, args.steps, args.warmup)
+
+    # ---- for reference: the streaming pass alone (csd_row_partials), same ring, same launch shape
+    part = csd.csd_row_partials(ring_z[0])
+    for i in range(args.warmup):
+        csd.csd_row_partials(ring_z[i % n_ring], part)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for i in range(args.steps):
+        csd.csd_row_partials(ring_z[(args.warmup + i) % n_ring], part)
+    ev1.record()
+    torch.cuda.synchronize()
+    k_ms = ev0.elapsed_time(ev1) / args.steps
+    alg_bytes = rows * cfg.V * cfg.itemsize            # every logit read once; outputs are a few KB
+    achieved = alg_bytes / (fused_ms * 1e-3) / 1e9      # the fused verify kernel, timed over the timed region
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_row_stream.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            rec = json.load(f)
+        ent = rec.get(cfg.name)
+        if ent and ent.get("kernel_fingerprint") == kernel_fingerprint():
+            traffic = ent["hbm_bytes_per_launch"]
+
+    out = {
+        "metric": "verified draft positions/sec + achieved HBM GB/s (% of peak) of csd_verify",
+        "value": value,
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": cfg.name, "B": cfg.B, "k": cfg.k, "V": cfg.V, "logits_storage": cfg.dtype,
+            "positions_per_step": rows, "draft_positions_per_step": cfg.B * cfg.k,
+            "tau": cfg.tau, "lambda": cfg.lam, "ocm_capacity": cfg.capacity, "ocm_updates": "applied",
+            "ring_steps": n_ring, "ring_bytes": n_ring * cfg.bytes_per_step,
+            "positions_per_s_without_ocm_updates": rows * args.steps / elapsed_noupd,
+            "ms_per_step_without_ocm_updates": elapsed_noupd / args.steps * 1e3,
+            "whole_path_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+            "whole_path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "accept_rate_last_step": accept_rate, "status_counters": status,
+            "input_generation_s": t_gen,
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "verify_kernel<%s, fused> (one launch per step)" % cfg.dtype, "achieved": achieved,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "kernel_ms": fused_ms, "algorithmic_bytes_per_launch": alg_bytes,
+            "streaming_pass_alone": {"kernel_ms": k_ms, "GBps": alg_bytes / (k_ms * 1e-3) / 1e9,
+                                     "frac": alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        },
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import csd_oracle as O
+        cores = min(16, len(os.sched_getaffinity(0)))
+        n_cpu_steps = len(ring_host)
+        if cfg.bytes_per_step < (64 << 20):          # small workloads: regenerate more steps for a stable number
+            extra = min(cfg.steps, max(4, int((256 << 20) // cfg.bytes_per_step)))
+            ring_host = [w.step(s, threads=args.gen_threads) for s in range(extra)]
+            n_cpu_steps = extra
+        orc = O.CSDOracle(capacity=cfg.capacity)
+        O.row_stats(ring_host[0][0][:1])             # load the library outside the timed part
+        t0 = time.perf_counter()
+        passes = 4 if cfg.bytes_per_step >= (64 << 20) else 1      # about 10-30 core-seconds in all
+        for _ in range(passes):
+            for z, d in ring_host:
+                orc.verify_step(z, d, tau=np.float32(cfg.tau), lam=cfg.lam, threads=cores)
+        n_cpu_steps *= passes
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": rows * n_cpu_steps / t_cpu, "unit": "positions/s", "cores": cores, "kind": "oracle",
+            "sample": "%d steps of %s (%d positions), fp64 oracle, rows split over %d threads, scan and memory serial"
+                      % (n_cpu_steps, cfg.name, rows * n_cpu_steps, cores),
+            "seconds": t_cpu,
+        }
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

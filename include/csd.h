@@ -83,10 +83,11 @@ extern "C" {
 #define CSD_POS_COUNTED 16u  /* pair handed to UpdateMemory                         */
 
 /*
- * Bytes of device scratch csd_verify needs for this shape (per-segment row partials and the
- * step's rejection log).  Returns 0 for invalid arguments.  Host function, no GPU work.
+ * Bytes of device scratch csd_verify needs for this shape (per-wave row partials, the step's
+ * rejection log and a completion ticket).  Returns 0 for invalid arguments.  Host function, no GPU work.
  */
 size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
+
 
 /*
  * csd_verify - one verification step for a batch (Algorithm 1, verification loop, temperature 0;
@@ -121,9 +122,13 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  *   rej_log     [B][k]    CSD_OCM_KEY(draft, t*) for each counted divergence, CSD_OCM_EMPTY elsewhere
  *                         (nullable; with flags == 0 it can be replayed later through csd_ocm_update).
  *   status      [CSD_STATUS_WORDS] counters, incremented (nullable).
+ * A step is two kernel launches: the streaming pass over the logits, then one wave per sequence for
+ * the verification logic; the wave that completes the batch applies the updates (batches of more than
+ * 8192 draft positions use a third launch for them).
  * Scratch
- *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; contents
- *                         are undefined afterwards.  Two calls in flight must not share a workspace.
+ *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; needs no
+ *                         initialisation, contents are undefined afterwards.  Two calls in flight must not
+ *                         share a workspace.
  * B == 0 is a valid no-op.  k == 0 verifies nothing and returns the argmax of the single row.
  */
 int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
@@ -153,6 +158,37 @@ int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream);
  */
 int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys, uint32_t *counts, uint64_t n,
                    void *stream);
+
+/*
+ * Row partials: the streaming pass over the logits on its own (the p_{1:gamma+1}(.) statistics of
+ * Algorithm 1 before any verification logic).  A row's tiles are dealt to several waves; each
+ * leaves one csd_row_partial for its share (an interleaved subset of the row, not a contiguous range).  A row's statistics follow from its partials as
+ *     m  = max_j m_j
+ *     t* = min{ idx_j : m_j == m }                       (float comparison)
+ *     S  = sum_j s_j * 2^(cref_j - m * CSD_LOG2E_F32)    (skip partials with s_j == 0)
+ * where CSD_LOG2E_F32 is log2(e) rounded to float, the constant the kernel multiplies logits by.
+ * The same combine merges vocabulary shards of a tensor-parallel LM head (offset idx by the shard base).
+ * csd_verify runs exactly this kernel as its first stage.
+ */
+typedef struct csd_row_partial {
+    float m;     /* maximum of the share, -inf if it holds no finite logit            */
+    float cref;  /* reference exponent (log2 units) that s is scaled by                */
+    float s;     /* sum over the share of 2^(z * CSD_LOG2E_F32 - cref)                 */
+    int32_t idx; /* lowest token id in the share whose logit equals m                  */
+} csd_row_partial;
+#define CSD_LOG2E_F32 1.4426950408889634f
+
+/* Partials per row that csd_row_partials writes for `rows` rows of V logits (0 = invalid shape). Host only. */
+int csd_row_partials_per_row(int rows, int V, int dtype);
+
+/*
+ * csd_row_partials - enqueue the streaming pass: partials[r * per_row + j], j < per_row, for r < rows.
+ *   logits, dtype, row_stride, V   as for csd_verify (rows are [rows][V], 16-byte aligned pitch)
+ *   partials                      device buffer of rows * csd_row_partials_per_row(rows,V,dtype) entries,
+ *                                 16-byte aligned; partials_bytes is its size (CSD_ENOSPACE if too small)
+ */
+int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows, int V, csd_row_partial *partials,
+                     size_t partials_bytes, void *stream);
 
 /* Static string for a return code (host pointer, never NULL). */
 const char *csd_strerror(int code);

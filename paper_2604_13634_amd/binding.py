@@ -62,6 +62,10 @@ def load_library() -> ctypes.CDLL:
     lib.csd_ocm_reset.argtypes = [vp, u64, vp]
     lib.csd_ocm_lookup.restype = i32
     lib.csd_ocm_lookup.argtypes = [vp, u64, vp, vp, u64, vp]
+    lib.csd_row_partials_per_row.restype = i32
+    lib.csd_row_partials_per_row.argtypes = [i32, i32, i32]
+    lib.csd_row_partials.restype = i32
+    lib.csd_row_partials.argtypes = [vp, i32, i64, i32, i32, vp, sz, vp]
     lib.csd_strerror.restype = ctypes.c_char_p
     lib.csd_strerror.argtypes = [i32]
     _lib = lib
@@ -198,6 +202,31 @@ def csd_ocm_lookup(ocm: torch.Tensor, keys: torch.Tensor, stream=None) -> torch.
     if rc != CSD_OK:
         raise CsdError(rc, "csd_ocm_lookup")
     return counts
+
+
+def csd_row_partials_per_row(rows: int, V: int, dtype: int) -> int:
+    return int(load_library().csd_row_partials_per_row(rows, V, dtype))
+
+
+def csd_row_partials(logits: torch.Tensor, partials: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Enqueue the streaming pass alone.  logits: [rows][V] or [B][k+1][V]; returns an int32 tensor
+    [rows][per_row][4] whose records are csd_row_partial {m, cref, s (float bits), idx}."""
+    V = logits.shape[-1]
+    rows = logits.numel() // V if V else 0
+    if logits.stride(-1) != 1:
+        raise ValueError("logits must have unit element stride")
+    row_stride = logits.stride(-2) if logits.dim() > 1 and rows > 1 else max(V, logits.stride(-2) if logits.dim() > 1 else V)
+    dt = _dtype_code(logits)
+    per_row = csd_row_partials_per_row(rows, V, dt)
+    if per_row == 0:
+        raise CsdError(CSD_EINVAL, "csd_row_partials_per_row")
+    if partials is None:
+        partials = torch.empty((rows, per_row, 4), dtype=torch.int32, device=logits.device)
+    rc = load_library().csd_row_partials(_ptr(logits), dt, row_stride, rows, V, _ptr(partials),
+                                         partials.numel() * 4, _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_row_partials")
+    return partials
 
 
 def decode_ocm(ocm: torch.Tensor) -> Dict[Tuple[int, int], int]:

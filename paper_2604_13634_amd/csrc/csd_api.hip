@@ -5,17 +5,6 @@
 #include "csd_internal.h"
 
 namespace csd {
-
-WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
-    WorkspaceLayout w;
-    w.partials_off = 0;
-    w.partials_bytes = (size_t)p.rows * (size_t)p.partials_per_row * sizeof(RowPartial);
-    w.log_off = (w.partials_off + w.partials_bytes + 255) & ~(size_t)255;
-    w.log_bytes = (size_t)B * (size_t)k * sizeof(uint64_t);
-    w.total = ((w.log_off + w.log_bytes + 255) & ~(size_t)255) + 256;   // never 0, so a valid shape is told from an invalid one
-    return w;
-}
-
 namespace {
 
 bool shape_ok(int B, int k, int V, int dtype) {
@@ -31,6 +20,8 @@ bool is_nan_bits(float f) {   // bit test: independent of the floating-point opt
     std::memcpy(&u, &f, sizeof u);
     return (u & 0x7FFFFFFFu) > 0x7F800000u;
 }
+constexpr uint64_t kMaxInKernelUpdates = 8192;   // log entries one wave applies at the end of the finish kernel
+
 bool is_pow2(uint64_t x) { return x != 0 && (x & (x - 1)) == 0; }
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -43,7 +34,7 @@ extern "C" {
 
 size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype) {
     if (!shape_ok(B, k, V, dtype)) return 0;
-    const StreamPlan p = make_stream_plan(B, k, V, dtype);
+    const StreamPlan p = make_stream_plan(B * (k + 1), V, dtype);
     return make_workspace_layout(p, B, k).total;
 }
 
@@ -67,7 +58,7 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
         !aligned(p_draft, 4) || !aligned(rej_log, 8) || !aligned(ocm, 8) || !aligned(status, 4))
         return CSD_EALIGN;
 
-    const StreamPlan plan = make_stream_plan(B, k, V, dtype);
+    const StreamPlan plan = make_stream_plan(B * (k + 1), V, dtype);
     const WorkspaceLayout ws = make_workspace_layout(plan, B, k);
     if (workspace_bytes < ws.total) return CSD_ENOSPACE;
 
@@ -75,8 +66,6 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     RowPartial *partials = (RowPartial *)((char *)workspace + ws.partials_off);
     const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
     uint64_t *log = rej_log ? rej_log : (apply ? (uint64_t *)((char *)workspace + ws.log_off) : nullptr);
-
-    if (launch_row_stream(logits, dtype, row_stride, V, plan, partials, st) != hipSuccess) return CSD_EHIP;
 
     EpilogueArgs a;
     a.logits = logits;
@@ -102,9 +91,14 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     a.pos_flags = pos_flags;
     a.rej_log = log;
     a.status = status;
-    if (launch_epilogue(a, st) != hipSuccess) return CSD_EHIP;
-
-    if (apply) {
+    a.batch_ticket = (uint32_t *)((char *)workspace + ws.ticket_off);
+    // The step's increments are applied inside the finish kernel by the wave that completes the batch;
+    // very large batches hand them to the bulk update kernel instead (one more launch, many workgroups).
+    const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
+    a.apply_updates = update_in_finish ? 1 : 0;
+    if (launch_row_partials(logits, dtype, row_stride, V, plan, partials, a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
+    if (launch_finish(a, st) != hipSuccess) return CSD_EHIP;
+    if (apply && !update_in_finish) {
         if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
     }
     return CSD_OK;
@@ -132,6 +126,23 @@ int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys,
     if (!keys || !counts) return CSD_EINVAL;
     if (!aligned(ocm, 8) || !aligned(keys, 8) || !aligned(counts, 4)) return CSD_EALIGN;
     return launch_ocm_lookup(ocm, capacity, keys, counts, n, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+int csd_row_partials_per_row(int rows, int V, int dtype) {
+    if (rows < 0 || !shape_ok(0, 0, V, dtype) || rows > (1 << 24)) return 0;
+    return make_stream_plan(rows, V, dtype).partials_per_row;
+}
+
+int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows, int V, csd_row_partial *partials,
+                     size_t partials_bytes, void *stream) {
+    if (rows < 0 || rows > (1 << 24) || !shape_ok(0, 0, V, dtype)) return CSD_EINVAL;
+    if (rows == 0) return CSD_OK;
+    if (!logits || !partials || row_stride < V) return CSD_EINVAL;
+    const size_t esz = (dtype == CSD_DTYPE_F32) ? 4 : 2;
+    if (!aligned(logits, 16) || ((size_t)row_stride * esz) % 16 != 0 || !aligned(partials, 16)) return CSD_EALIGN;
+    const StreamPlan plan = make_stream_plan(rows, V, dtype);
+    if (partials_bytes < (size_t)rows * plan.partials_per_row * sizeof(RowPartial)) return CSD_ENOSPACE;
+    return launch_row_partials(logits, dtype, row_stride, V, plan, partials, nullptr, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
 const char *csd_strerror(int code) {

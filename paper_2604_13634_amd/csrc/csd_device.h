@@ -1,0 +1,129 @@
+// Device-side helpers: wave-wide reductions and the Online Correction Memory slot operations.
+#pragma once
+
+#include "csd_internal.h"
+
+namespace csd {
+
+// ---- wave-wide all-reduces: DPP inside a row of 16 lanes, ds_swizzle across rows, bpermute across halves.
+// Every lane ends up with the result (both partners of a step compute op(own, other), and op is commutative).
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ int xor16_i(int v) { return __builtin_amdgcn_ds_swizzle(v, 0x401F); }   // lane ^ 16
+__device__ __forceinline__ int xor32_i(int v) {
+    return __builtin_amdgcn_ds_bpermute(((int)__lane_id() ^ 32) << 2, v);
+}
+
+template <typename Op>
+__device__ __forceinline__ float wave_allreduce_f(float v, Op op) {
+    v = op(v, __int_as_float(dpp_i<0xB1>(__float_as_int(v))));    // quad_perm [1,0,3,2]
+    v = op(v, __int_as_float(dpp_i<0x4E>(__float_as_int(v))));    // quad_perm [2,3,0,1]
+    v = op(v, __int_as_float(dpp_i<0x141>(__float_as_int(v))));   // row_half_mirror (quads are uniform now)
+    v = op(v, __int_as_float(dpp_i<0x140>(__float_as_int(v))));   // row_mirror      (halves are uniform now)
+    v = op(v, __int_as_float(xor16_i(__float_as_int(v))));
+    v = op(v, __int_as_float(xor32_i(__float_as_int(v))));
+    return v;
+}
+template <typename Op>
+__device__ __forceinline__ int wave_allreduce_i(int v, Op op) {
+    v = op(v, dpp_i<0xB1>(v));
+    v = op(v, dpp_i<0x4E>(v));
+    v = op(v, dpp_i<0x141>(v));
+    v = op(v, dpp_i<0x140>(v));
+    v = op(v, xor16_i(v));
+    v = op(v, xor32_i(v));
+    return v;
+}
+struct MaxF { __device__ float operator()(float a, float b) const { return __builtin_fmaxf(a, b); } };
+struct AddF { __device__ float operator()(float a, float b) const { return a + b; } };
+struct MinI { __device__ int operator()(int a, int b) const { return a < b ? a : b; } };
+
+// lane ^ mask exchange for any mask < 64 (bpermute); used off the hot loop only
+__device__ __forceinline__ int xchg_i(int v, int mask) {
+    return __builtin_amdgcn_ds_bpermute(((int)__lane_id() ^ mask) << 2, v);
+}
+__device__ __forceinline__ float xchg_f(float v, int mask) { return __int_as_float(xchg_i(__float_as_int(v), mask)); }
+__device__ __forceinline__ double xchg_d(double v, int mask) {
+    const long long b = __double_as_longlong(v);
+    const int lo = xchg_i((int)(b & 0xFFFFFFFFll), mask), hi = xchg_i((int)(b >> 32), mask);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// value held by lane `src`
+__device__ __forceinline__ int from_lane_i(int v, int src) { return __builtin_amdgcn_ds_bpermute(src << 2, v); }
+__device__ __forceinline__ float from_lane_f(float v, int src) { return __int_as_float(from_lane_i(__float_as_int(v), src)); }
+__device__ __forceinline__ double from_lane_d(double v, int src) {
+    const long long b = __double_as_longlong(v);
+    const int lo = from_lane_i((int)(b & 0xFFFFFFFFll), src), hi = from_lane_i((int)(b >> 32), src);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+// ---- Online Correction Memory slots (layout in csd.h)
+__device__ __forceinline__ uint64_t slot_key(uint64_t s) { return s & CSD_OCM_KEY_MASK; }
+__device__ __forceinline__ uint32_t slot_count(uint64_t s) { return (uint32_t)(s >> CSD_OCM_KEY_BITS); }
+
+// Fibonacci hashing of the 40-bit key; capacity is a power of two.
+__device__ __forceinline__ uint64_t home_slot(uint64_t key, uint64_t capacity) {
+    const uint64_t h = key * 0x9E3779B97F4A7C15ull;
+    return (h >> 20) & (capacity - 1);
+}
+
+// T[key], 0 if absent.  Linear probing; an empty slot ends the search (there is no deletion).
+__device__ inline uint32_t ocm_lookup(const uint64_t *ocm, uint64_t capacity, uint64_t key) {
+    uint64_t i = home_slot(key, capacity);
+    for (uint64_t probe = 0; probe < capacity; ++probe) {
+        const uint64_t s = __hip_atomic_load(&ocm[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t sk = slot_key(s);
+        if (sk == key) return slot_count(s);
+        if (sk == CSD_OCM_EMPTY) return 0;
+        i = (i + 1) & (capacity - 1);
+    }
+    return 0;
+}
+
+// T[key] += w (saturating), inserting the key if absent.  Returns false when every slot holds another key.
+__device__ inline bool ocm_add(uint64_t *ocm, uint64_t capacity, uint64_t key, uint32_t w) {
+    uint64_t i = home_slot(key, capacity);
+    for (uint64_t probe = 0; probe < capacity; ++probe) {
+        uint64_t cur = __hip_atomic_load(&ocm[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (;;) {
+            const uint64_t ck = slot_key(cur);
+            if (ck != key && ck != CSD_OCM_EMPTY) break;              // another pair lives here: next slot
+            uint64_t cnt = (ck == key) ? (uint64_t)slot_count(cur) : 0ull;
+            cnt += w;
+            if (cnt > CSD_OCM_COUNT_MAX) cnt = CSD_OCM_COUNT_MAX;
+            const uint64_t want = key | (cnt << CSD_OCM_KEY_BITS);
+            if (__hip_atomic_compare_exchange_strong(&ocm[i], &cur, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT))
+                return true;
+            // lost a race: `cur` now holds the slot's new content; look at it again
+        }
+        i = (i + 1) & (capacity - 1);
+    }
+    return false;
+}
+
+// LDS pre-aggregation table: distinct keys of a batch of log entries with their summed weights.
+constexpr int kLdsSlots = 1024;                // >= 2 * entries aggregated at a time: never fills
+constexpr int kLdsBatch = kLdsSlots / 2;
+
+__device__ __forceinline__ void lds_aggregate(unsigned long long *lkey, unsigned long long *lcnt, uint64_t key, uint32_t w) {
+    uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) & (kLdsSlots - 1);
+    for (;;) {
+        unsigned long long cur = lkey[i];
+        if (cur == CSD_OCM_EMPTY) cur = atomicCAS(&lkey[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
+        if (cur == CSD_OCM_EMPTY || cur == key) {
+            atomicAdd(&lcnt[i], (unsigned long long)w);
+            return;
+        }
+        i = (i + 1) & (kLdsSlots - 1);
+    }
+}
+
+__device__ __forceinline__ float load_logit(const void *logits, int dtype, int64_t elem) {
+    if (dtype == CSD_DTYPE_F32) return ((const float *)logits)[elem];
+    return __uint_as_float((uint32_t)((const uint16_t *)logits)[elem] << 16);
+}
+
+}  // namespace csd

@@ -9,38 +9,32 @@
 
 namespace csd {
 
-// One wave's result for one segment of a logits row.
-//   m    : maximum of the segment (-inf when the segment holds no finite value)
-//   cref : reference exponent, in log2 units, that `s` is scaled by
-//   s    : sum over the segment of 2^(z * log2e - cref)
-//   idx  : lowest token id in the segment whose logit equals m
-struct __attribute__((aligned(16))) RowPartial {
-    float m;
-    float cref;
-    float s;
-    int32_t idx;
-};
+// One wave's result for its share of a logits row (public layout, see csd.h).
+using RowPartial = csd_row_partial;
+static_assert(sizeof(RowPartial) == 16, "partials are read and written as 16-byte records");
 
 constexpr int kWaveSize = 64;
-constexpr int kStreamWaves = 4;              // waves per row-stream workgroup
-constexpr int kStreamUnroll = 4;             // 16-byte loads in flight per lane
-constexpr int kTileChunks = kStreamWaves * kWaveSize * kStreamUnroll;   // 16-byte chunks per workgroup iteration
-constexpr int kTargetBlocks = 2048;          // row-stream grid size aimed at (8 per CU on 256 CUs)
+constexpr int kStreamWaves = 4;              // waves per workgroup of the verify kernel
+constexpr int kStreamUnroll = 8;             // 16-byte loads in flight per lane
+constexpr int kTileChunks = kStreamWaves * kWaveSize * kStreamUnroll;   // 16-byte chunks per workgroup iteration (32 KiB)
 
-// Launch plan of the row-stream kernel; a pure function of the shape so that the
-// workspace size query and the launch agree.
+// Launch plan of the streaming pass; a pure function of the shape so that the workspace size query and
+// the launch agree.  A row's whole tiles are dealt round-robin to `nsplit` workgroups; the workgroup
+// (ntiles_row % nsplit) also takes the remainder (chunks past the last whole tile, ragged one included).
 struct StreamPlan {
-    int rows;              // B * (k + 1)
+    int rows;              // verify rows, B * (k + 1)
     int elems_per_chunk;   // 4 (fp32) or 8 (bf16) logits per 16-byte chunk
     int nchunks;           // chunks per row, the ragged last one included
-    int nsplit;            // segments per row
-    int chunks_per_split;  // multiple of kTileChunks
-    int partials_per_row;  // nsplit * kStreamWaves
+    int ntiles_row;        // whole tiles of whole chunks per row
+    int nsplit;            // workgroups per row
+    int partials_per_row;  // nsplit * kStreamWaves: one partial per wave
 };
 
-StreamPlan make_stream_plan(int B, int k, int V, int dtype);
+StreamPlan make_stream_plan(int rows, int V, int dtype);
 
+// csd_verify workspace: [batch ticket | partials | rejection log].  Nothing in it outlives a call.
 struct WorkspaceLayout {
+    size_t ticket_off;
     size_t partials_off, partials_bytes;
     size_t log_off, log_bytes;
     size_t total;
@@ -48,19 +42,16 @@ struct WorkspaceLayout {
 
 WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k);
 
-// kernel launchers (enqueue only; return hipGetLastError())
-hipError_t launch_row_stream(const void *logits, int dtype, int64_t row_stride, int V, const StreamPlan &plan,
-                             RowPartial *partials, hipStream_t stream);
-
+// Everything the per-sequence epilogue and the update phase need.
 struct EpilogueArgs {
     const void *logits;
     int dtype;
-    int64_t row_stride;
+    int64_t row_stride;      // elements
     const int32_t *draft;
     int B, k, V;
     float tau;
     uint32_t lambda;
-    const uint64_t *ocm;
+    uint64_t *ocm;           // NULL: no memory
     uint64_t capacity;
     const RowPartial *partials;
     int partials_per_row;
@@ -72,11 +63,16 @@ struct EpilogueArgs {
     float *ratio;
     float *p_draft;
     uint8_t *pos_flags;
-    uint64_t *rej_log;      // user log or workspace log, may be NULL when nothing needs it
+    uint64_t *rej_log;       // user log or workspace log; NULL when nothing needs it
     uint32_t *status;
+    uint32_t *batch_ticket;  // [1], zero when the finish kernel starts
+    int apply_updates;
 };
 
-hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream);
+// kernel launchers (enqueue only; return hipGetLastError())
+hipError_t launch_row_partials(const void *logits, int dtype, int64_t row_stride, int V, const StreamPlan &plan,
+                               RowPartial *partials, uint32_t *batch_ticket, hipStream_t stream);
+hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream);
 hipError_t launch_ocm_reset(uint64_t *ocm, uint64_t capacity, hipStream_t stream);

@@ -1,0 +1,477 @@
+// The verification step: two launches per decode step.
+//
+// Kernel 1 - streaming pass (row_partials_kernel).  For every verify row (a draft position or the bonus
+// row of Algorithm 1) the step needs the target distribution's normaliser, the greedy target token t*
+// and, later, single probabilities (Eq. 3 and the p_i(.) of Algorithm 1):
+//     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
+// Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
+// kernel is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are dealt round-robin
+// to `nsplit` workgroups of 4 waves, so the workgroups of a row sweep it side by side; inside a tile the
+// waves interleave 1 KiB wave-loads.  Each wave keeps its own running state and writes one partial;
+// there is no barrier and no cross-wave step in this kernel.
+//
+//   Per-lane state (fp32): rm = running maximum; best_q = the 16-byte chunk at which rm last strictly
+//   increased and best_it = its iteration, i.e. the first chunk of this lane that holds rm (a lane
+//   visits chunks in ascending address order, so "first" is "lowest token id"); s[E] = sums of
+//   2^(z*log2e - c), one per element slot of a chunk, against a WAVE-UNIFORM reference exponent c.
+//   c is not the running maximum: it is only kept within kRescaleGap of it, which is all floating point
+//   needs (no overflow, full relative precision).  A rescale (wave reduction + multiply) happens only
+//   when some lane's maximum climbs more than kRescaleGap above the reference - at the first tile, then
+//   almost never - so the steady-state loop is unpack, max3, fma, v_exp_f32, add and one compare per
+//   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
+//   c itself is carried exactly into the combine.
+//
+// Kernel 2 - finish (finish_kernel), one wave per sequence: combine the row partials (normaliser in
+// double), draft-token ratio and probability (Eq. 3), memory lookup then gate (Algorithm 1),
+// accepted-prefix scan by ballot, emitted token, and the list of divergences to count.  Each wave then
+// takes a ticket on the batch; the wave that draws the last ticket knows that every lookup of the step
+// has been made and applies the step's increments, so all lookups read the table as it stood when the
+// step began.  No wave waits for another.  The log handed from the sequence waves to the updating wave
+// is written with agent-scope atomic stores (write-through to where the eight XCDs' L2s agree) and read
+// back with agent-scope atomic loads; a writer waits for its stores to be acknowledged before it draws
+// its ticket, itself an agent-scope atomic add.  (A release/acquire fence pair would do the same job by
+// writing back and invalidating a whole L2 per wave, which measured ten times the streaming pass.)
+#include "csd_device.h"
+
+namespace csd {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = CSD_LOG2E_F32;
+constexpr double kLog2eD = (double)CSD_LOG2E_F32;
+constexpr float kRescaleGap = 20.0f;   // logit units; 20*log2e < 32 keeps the exponent's ulp at 2^-19 or finer
+constexpr int kNoIter = 0x7fffffff;
+constexpr int kRemIter = 1 << 30;      // best_it values at or above this index the remainder loop
+
+// ---- 16-byte chunk of logits -> fp32 values (bf16 widening is exact)
+template <int DT> struct Chunk;
+template <> struct Chunk<CSD_DTYPE_F32> {
+    static constexpr int E = 4;
+    static constexpr uint32_t kNegInfWord = 0xFF800000u;
+    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
+        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
+        x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+    }
+    // the last, partial chunk of a row: n < E logits starting at element v0, the rest -inf
+    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
+        const uint32_t *p = (const uint32_t *)row + v0;
+        u32x4 q = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+        if (n > 0) q.x = p[0];
+        if (n > 1) q.y = p[1];
+        if (n > 2) q.z = p[2];
+        return q;
+    }
+};
+template <> struct Chunk<CSD_DTYPE_BF16> {
+    static constexpr int E = 8;
+    static constexpr uint32_t kNegInfWord = 0xFF80FF80u;
+    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
+        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xFFFF0000u);
+        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xFFFF0000u);
+        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xFFFF0000u);
+        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xFFFF0000u);
+    }
+    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
+        const uint16_t *p = (const uint16_t *)row + v0;
+        uint32_t w[4] = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+#pragma unroll
+        for (int j = 0; j < 7; ++j) {
+            if (j < n) {
+                const uint32_t h = p[j];
+                w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | (h << 16)) : ((w[j >> 1] & 0xFFFF0000u) | h);
+            }
+        }
+        u32x4 q = {w[0], w[1], w[2], w[3]};
+        return q;
+    }
+};
+
+template <int E>
+__device__ __forceinline__ float chunk_max(const float (&x)[E]) {
+    float m = x[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) m = __builtin_fmaxf(m, x[j]);
+    return m;
+}
+
+// ---- data handed between workgroups: agent-scope relaxed atomics, 64 bits at a time
+__device__ __forceinline__ void xwg_store64(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t xwg_load64(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One atomic ticket: true in every lane of the wave that drew the last of `total` tickets.
+// Before the ticket the wave waits until its earlier stores are acknowledged (workgroup-scope release =
+// s_waitcnt, and a compiler barrier); after it a workgroup-scope acquire keeps later loads from moving up.
+__device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int lane) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    int last = 0;
+    if (lane == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = (old == total - 1);
+    }
+    last = __builtin_amdgcn_readfirstlane(last);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return last != 0;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Phase 1: this wave's share of one row -> one RowPartial (returned in lane-uniform registers).
+template <int DT>
+__device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ rowp, int V, int nsplit, int split,
+                                                       int wave, int lane) {
+    using C = Chunk<DT>;
+    constexpr int E = C::E;
+    constexpr int W = kStreamWaves;
+    constexpr int U = kStreamUnroll;
+    constexpr int WL = W * kWaveSize;              // chunks one load instruction of the workgroup covers
+
+    const int nfull = V / E;                       // whole 16-byte chunks of the row
+    const int tail = V - nfull * E;                // logits in the ragged last chunk
+    const int nchunks = nfull + (tail ? 1 : 0);
+    const int ntiles_row = nfull / kTileChunks;    // whole tiles of whole chunks
+    const int rem0 = ntiles_row * kTileChunks;     // first chunk of the remainder
+    const bool has_rem = (split == ntiles_row % nsplit) && (rem0 < nchunks);
+    const int ntiles = (ntiles_row > split) ? (ntiles_row - split + nsplit - 1) / nsplit : 0;   // tiles split, split+nsplit, ...
+
+    float rm = -INFINITY;      // running max of this lane
+    int best_it = kNoIter;     // iteration that first reached rm ...
+    u32x4 best_q = {0u, 0u, 0u, 0u};   // ... and the chunk read there
+    float s[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) s[j] = 0.f;
+    float c = 0.f;             // wave-uniform reference exponent (log2 units)
+    float mth = -INFINITY;     // rescale when a lane maximum exceeds this
+    const int lane_chunk0 = wave * kWaveSize + lane;
+
+    auto rescale = [&]() {
+        const float wm = wave_allreduce_f(rm, MaxF());
+        const float cn = wm * kLog2e;
+        const float sc = __builtin_amdgcn_exp2f(c - cn);
+#pragma unroll
+        for (int j = 0; j < E; ++j) s[j] = (s[j] == 0.f) ? 0.f : s[j] * sc;
+        c = cn;
+        mth = wm + kRescaleGap;
+    };
+
+    // ---- whole tiles: U independent non-temporal 16-byte loads per lane.
+    // Local tile t is row tile split + t*nsplit; its chunk for (u, this lane) is
+    //     (split + t*nsplit) * kTileChunks + u*WL + lane_chunk0   < ntiles_row * kTileChunks <= nfull.
+    const u32x4 *p = (const u32x4 *)rowp + (size_t)split * kTileChunks + lane_chunk0;
+    for (int t = 0; t < ntiles; ++t) {
+        u32x4 q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(p + u * WL);
+        p += (size_t)nsplit * kTileChunks;
+
+        float x[U][E];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            C::unpack(q[u], x[u]);
+            const float cm = chunk_max<E>(x[u]);
+            const bool up = cm > rm;
+            best_it = up ? (t * U + u) : best_it;
+            best_q.x = up ? q[u].x : best_q.x;
+            best_q.y = up ? q[u].y : best_q.y;
+            best_q.z = up ? q[u].z : best_q.z;
+            best_q.w = up ? q[u].w : best_q.w;
+            rm = __builtin_fmaxf(rm, cm);
+        }
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(rm > mth) != 0, 0)) rescale();
+        const float nc = -c;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][j], kLog2e, nc));
+        }
+    }
+
+    // ---- remainder of the row (one workgroup per row): one guarded chunk per lane per iteration;
+    // slots past V are filled with -inf, the ragged chunk is read element by element.
+    if (has_rem) {
+        for (int it = 0; rem0 + it * WL < nchunks; ++it) {
+            const int ch = rem0 + it * WL + lane_chunk0;
+            u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
+            if (ch < nfull) {
+                q = ((const u32x4 *)rowp)[ch];
+            } else if (ch == nfull) {
+                q = C::load_ragged(rowp, nfull * E, tail);
+            }
+            float x[E];
+            C::unpack(q, x);
+            const float cm = chunk_max<E>(x);
+            const bool up = cm > rm;
+            best_it = up ? (kRemIter + it) : best_it;
+            best_q.x = up ? q.x : best_q.x;
+            best_q.y = up ? q.y : best_q.y;
+            best_q.z = up ? q.z : best_q.z;
+            best_q.w = up ? q.w : best_q.w;
+            rm = __builtin_fmaxf(rm, cm);
+            if (__builtin_amdgcn_ballot_w64(rm > mth) != 0) rescale();
+            const float nc = -c;
+#pragma unroll
+            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], kLog2e, nc));
+        }
+    }
+
+    // ---- wave result
+    float sl = s[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) sl += s[j];
+    const float ws = wave_allreduce_f(sl, AddF());
+    const float wm = wave_allreduce_f(rm, MaxF());
+    // Lanes that hold the wave maximum name the lowest token id at which they saw it: the first element
+    // of their saved chunk equal to it (float compare: -0 == +0).  The wave takes the smallest.
+    int my_idx = kNoIter;
+    if (best_it != kNoIter && rm == wm) {
+        const int chunk = (best_it >= kRemIter)
+                              ? rem0 + (best_it - kRemIter) * WL + lane_chunk0
+                              : ((best_it / U) * nsplit + split) * kTileChunks + (best_it % U) * WL + lane_chunk0;
+        float x[E];
+        C::unpack(best_q, x);
+        int j0 = E - 1;
+#pragma unroll
+        for (int j = E - 1; j >= 0; --j) j0 = (x[j] == wm) ? j : j0;
+        my_idx = chunk * E + j0;
+    }
+    int idx = wave_allreduce_i(my_idx, MinI());
+    // a share without any finite value reports the first token it covers (token 0 if it covers nothing)
+    if (idx == kNoIter) idx = ((split < ntiles_row) ? split * kTileChunks : (has_rem ? rem0 : 0)) * E;
+    RowPartial out;
+    out.m = wm;
+    out.cref = c;
+    out.s = ws;
+    out.idx = idx;
+    return out;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Phase 2: one wave, one sequence (all 64 lanes active on entry).
+__device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, int lane) {
+    const int k = a.k, K1 = a.k + 1, P = a.partials_per_row;
+    const bool is_pos = lane < k;
+
+    // draft token and its logit first: independent of the partials, so the latencies overlap
+    int d = -1;
+    bool valid = false;
+    float zd = 0.f;
+    if (is_pos) {
+        d = a.draft[(int64_t)b * k + lane];
+        valid = (d >= 0) && (d < a.V);
+        if (valid) zd = load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
+    }
+
+    // ---- combine the partials: G lanes share a row, then a butterfly inside each group of G
+    int G = 1;
+    while (2 * G * K1 <= kWaveSize) G *= 2;
+    const int grow = lane / G, gs = lane & (G - 1);
+    const bool active = grow < K1;
+    const RowPartial *pp = a.partials + ((int64_t)b * K1 + (active ? grow : 0)) * P;
+    float m = -INFINITY;
+    for (int j = gs; j < P; j += G) m = fmaxf(m, pp[j].m);
+    float gm = m;
+    for (int x = 1; x < G; x <<= 1) gm = fmaxf(gm, xchg_f(gm, x));
+    const double mref = (double)gm * kLog2eD;
+    int t = 0x7fffffff;
+    double S = 0.0;
+    for (int j = gs; j < P; j += G) {
+        const RowPartial q = pp[j];
+        if (q.m == gm && q.idx < t) t = q.idx;
+        if (q.s != 0.f) S += (double)q.s * exp2((double)q.cref - mref);
+    }
+    for (int x = 1; x < G; x <<= 1) {
+        S += xchg_d(S, x);
+        const int ot = xchg_i(t, x);
+        t = ot < t ? ot : t;
+    }
+    if (active && gs == 0) {
+        const int64_t row = (int64_t)b * K1 + grow;
+        a.argmax[row] = t;
+        if (a.row_max) a.row_max[row] = gm;
+        if (a.row_sumexp) a.row_sumexp[row] = (float)S;
+    }
+    // position layout: lane i takes the statistics of row i (lanes >= K1 read row 0, unused)
+    const int src = (lane < K1 ? lane : 0) * G;
+    const float rmax = from_lane_f(gm, src);
+    const int tstar = from_lane_i(t, src);
+    const double rS = from_lane_d(S, src);
+
+    // ---- Eq. 3: ratio = p(draft)/p(t*) = exp(z_draft - m); p(draft) = ratio / S
+    double ratio = 0.0;
+    if (is_pos) {
+        if (valid) ratio = exp2(((double)zd - (double)rmax) * 1.4426950408889634);
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.ratio) a.ratio[o] = (float)ratio;
+        if (a.p_draft) a.p_draft[o] = (float)(ratio / rS);
+    }
+
+    // ---- Algorithm 1: match, else memory lookup and gate
+    const bool match = is_pos && (d == tstar);
+    const bool diverges = is_pos && valid && !match;
+    const uint64_t key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? tstar : 0));
+    bool is_freq = false;
+    if (diverges && a.ocm != nullptr)   // lambda == 0 makes every pair frequent without touching the table
+        is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, key) >= a.lambda);
+    const bool is_safe = diverges && (ratio >= (double)a.tau);
+    const bool ok = match || (is_freq && is_safe);
+
+    // ---- accepted prefix, emitted token, divergences to count (every processed one, rescued or not)
+    const uint64_t fail = __builtin_amdgcn_ballot_w64(is_pos && !ok) | (1ull << k);
+    const int n = (int)__builtin_ctzll(fail);                  // first failing position, k if none
+    const bool processed = is_pos && (lane <= n);
+    const bool counted = processed && diverges;
+    const int next = from_lane_i(tstar, n);                    // row n: stopping position or bonus row
+
+    if (is_pos) {
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.pos_flags) {
+            uint8_t f = 0;
+            if (processed) {
+                if (match) f = CSD_POS_MATCH | CSD_POS_ACCEPTED;
+                else if (diverges)
+                    f = CSD_POS_COUNTED | (is_freq ? CSD_POS_FREQ : 0) | (is_safe ? CSD_POS_SAFE : 0) |
+                        (ok ? CSD_POS_ACCEPTED : 0);
+            }
+            a.pos_flags[o] = f;
+        }
+        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? key : CSD_OCM_EMPTY);   // read by the update wave
+    }
+    const uint64_t m_counted = __builtin_amdgcn_ballot_w64(counted);
+    const uint64_t m_rescued = __builtin_amdgcn_ballot_w64(counted && ok);
+    const uint64_t m_bad = __builtin_amdgcn_ballot_w64(processed && !valid);
+    if (lane == 0) {
+        a.accept_len[b] = n;
+        a.next_token[b] = next;
+        if (a.status) {
+            if (m_bad) atomicAdd(&a.status[CSD_STATUS_BAD_DRAFT], (uint32_t)__builtin_popcountll(m_bad));
+            if (m_rescued) atomicAdd(&a.status[CSD_STATUS_RESCUED], (uint32_t)__builtin_popcountll(m_rescued));
+            if (m_counted) atomicAdd(&a.status[CSD_STATUS_COUNTED], (uint32_t)__builtin_popcountll(m_counted));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Phase 3: one wave applies the step's log (n entries) to the table.  Duplicates are merged in an LDS
+// table first, so a skewed step costs one compare-and-swap chain per distinct pair.
+__device__ __forceinline__ void wave_apply_log(const EpilogueArgs &a, unsigned long long *lkey, unsigned long long *lcnt,
+                                               int lane) {
+    const int64_t n = (int64_t)a.B * a.k;
+    if (n <= kWaveSize) {                           // tiny step: no aggregation
+        const uint64_t key = (lane < n) ? (xwg_load64(&a.rej_log[lane]) & CSD_OCM_KEY_MASK) : CSD_OCM_EMPTY;
+        if (key != CSD_OCM_EMPTY && !ocm_add(a.ocm, a.capacity, key, 1u) && a.status)
+            atomicAdd(&a.status[CSD_STATUS_DROPPED], 1u);
+        return;
+    }
+    for (int64_t base = 0; base < n; base += kLdsBatch) {
+        for (int i = lane; i < kLdsSlots; i += kWaveSize) {
+            lkey[i] = CSD_OCM_EMPTY;
+            lcnt[i] = 0;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        uint64_t ent[kLdsBatch / kWaveSize];         // all loads first, then the LDS work
+#pragma unroll
+        for (int j = 0; j < kLdsBatch / kWaveSize; ++j) {
+            const int64_t e = base + j * kWaveSize + lane;
+            ent[j] = (e < n) ? (xwg_load64(&a.rej_log[e]) & CSD_OCM_KEY_MASK) : CSD_OCM_EMPTY;
+        }
+#pragma unroll
+        for (int j = 0; j < kLdsBatch / kWaveSize; ++j)
+            if (ent[j] != CSD_OCM_EMPTY) lds_aggregate(lkey, lcnt, ent[j], 1u);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int i = lane; i < kLdsSlots; i += kWaveSize) {
+            const unsigned long long key = lkey[i];
+            if (key == CSD_OCM_EMPTY) continue;
+            const uint32_t w = (uint32_t)lcnt[i];
+            if (!ocm_add(a.ocm, a.capacity, key, w) && a.status) atomicAdd(&a.status[CSD_STATUS_DROPPED], w);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kernel(const char *__restrict__ logits,
+                                                                                  int64_t row_pitch_bytes, int V, int nsplit,
+                                                                                  RowPartial *__restrict__ partials,
+                                                                                  uint32_t *batch_ticket) {
+    const int row = blockIdx.x / nsplit;
+    const int split = blockIdx.x - row * nsplit;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    // the finish kernel's ticket starts every step at zero (kernel order makes this visible to it)
+    if (batch_ticket != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(batch_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    const RowPartial out = stream_row_share<DT>(logits + (int64_t)row * row_pitch_bytes, V, nsplit, split, wave, lane);
+    if (lane == 0) partials[((int64_t)row * nsplit + split) * kStreamWaves + wave] = out;   // one 16-byte store
+}
+
+constexpr int kFinishWaves = 4;
+
+__global__ __launch_bounds__(kFinishWaves *kWaveSize) void finish_kernel(EpilogueArgs a) {
+    __shared__ unsigned long long lkey[kLdsSlots];
+    __shared__ unsigned long long lcnt[kLdsSlots];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    if (b >= a.B) return;                           // whole wave leaves together
+    sequence_epilogue(a, b, lane);
+    if (!a.apply_updates) return;
+    if (!take_last_ticket(a.batch_ticket, (uint32_t)a.B, lane)) return;
+    wave_apply_log(a, lkey, lcnt, lane);            // every lookup of the step has been made
+}
+
+}  // namespace
+
+StreamPlan make_stream_plan(int rows, int V, int dtype) {
+    StreamPlan p;
+    p.rows = rows;
+    p.elems_per_chunk = (dtype == CSD_DTYPE_F32) ? 4 : 8;
+    p.nchunks = (V + p.elems_per_chunk - 1) / p.elems_per_chunk;
+    p.ntiles_row = (V / p.elems_per_chunk) / kTileChunks;
+    // Workgroups per row: one tile each while the launch is small (latency matters, fill the chip),
+    // about four tiles each once there are thousands of tiles (fewer partials and tickets per byte).
+    const int64_t tiles_total = (int64_t)rows * (p.ntiles_row > 0 ? p.ntiles_row : 1);
+    const int tiles_per_group = tiles_total >= 16384 ? 4 : (tiles_total >= 4096 ? 2 : 1);
+    int nsplit = (p.ntiles_row + tiles_per_group - 1) / tiles_per_group;
+    if (nsplit < 1) nsplit = 1;
+    p.nsplit = nsplit;
+    p.partials_per_row = p.nsplit * kStreamWaves;
+    return p;
+}
+
+WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
+    WorkspaceLayout w;
+    w.ticket_off = 0;                              // one uint32, written by kernel 1, drawn in kernel 2
+    w.partials_off = 256;
+    w.partials_bytes = (size_t)p.rows * (size_t)p.partials_per_row * sizeof(RowPartial);
+    w.log_off = (w.partials_off + w.partials_bytes + 255) & ~(size_t)255;
+    w.log_bytes = (size_t)B * (size_t)k * sizeof(uint64_t);
+    w.total = (w.log_off + w.log_bytes + 255) & ~(size_t)255;
+    return w;
+}
+
+hipError_t launch_row_partials(const void *logits, int dtype, int64_t row_stride, int V, const StreamPlan &plan,
+                               RowPartial *partials, uint32_t *batch_ticket, hipStream_t stream) {
+    if (plan.rows == 0) return hipSuccess;
+    const dim3 grid((unsigned)(plan.rows * plan.nsplit)), block(kStreamWaves * kWaveSize);
+    if (dtype == CSD_DTYPE_F32)
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, (const char *)logits, row_stride * 4, V,
+                           plan.nsplit, partials, batch_ticket);
+    else
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, (const char *)logits, row_stride * 2, V,
+                           plan.nsplit, partials, batch_ticket);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream) {
+    if (a.B == 0) return hipSuccess;
+    const dim3 grid((unsigned)((a.B + kFinishWaves - 1) / kFinishWaves));
+    hipLaunchKernelGGL(finish_kernel, grid, dim3(kFinishWaves * kWaveSize), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace csd

@@ -321,3 +321,71 @@ def test_verify_on_a_side_stream():
     orc = O.CSDOracle()
     compare_step(orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=cfg.lam), bf, "side stream")
     compare_table(ocm, orc)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_row_partials_combine_to_the_row_statistics(dtype):
+    """csd_row_partials alone: combining the documented records on the host (fp64) gives the oracle's
+    m, t*, S - also when the rows are two vocabulary shards merged with an index offset."""
+    rng = np.random.default_rng(31)
+    rows, V = 37, 48008
+    z = (rng.standard_normal((rows, V)) * 3).astype(np.float32)
+    z[np.arange(rows), rng.integers(0, V, rows)] += 9.0
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z).reshape(rows, V)
+    m, t, S = O.row_stats(z)
+    L = float(np.float32(1.4426950408889634))
+
+    def combine(recs, offsets):
+        mm = max(float(r[0]) for r in recs)
+        idx = min(int(r[3]) + off for r, off in zip(recs, offsets) if float(r[0]) == mm)
+        tot = sum(float(r[2]) * 2.0 ** (float(r[1]) - mm * L) for r in recs if float(r[2]) != 0.0)
+        return mm, idx, tot
+
+    def records(part_row):
+        f = part_row.view(np.float32)
+        return [(f[j, 0], f[j, 1], f[j, 2], part_row[j, 3]) for j in range(part_row.shape[0])]
+
+    part = csd.csd_row_partials(to_device_logits(z))
+    torch.cuda.synchronize()
+    part = part.cpu().numpy()
+    assert part.shape[1] == csd.csd_row_partials_per_row(rows, V, 0 if dtype == "f32" else 1)
+    for r in range(rows):
+        mm, idx, tot = combine(records(part[r]), [0] * part.shape[1])
+        assert mm == m[r] and idx == t[r]
+        assert tot == pytest.approx(S[r], rel=1e-5)
+
+    # two shards of the vocabulary, reduced separately, merged with the shard base added to idx
+    half = 24000
+    pa = csd.csd_row_partials(to_device_logits(np.ascontiguousarray(z[:, :half]))).cpu().numpy()
+    pb = csd.csd_row_partials(to_device_logits(np.ascontiguousarray(z[:, half:]))).cpu().numpy()
+    for r in range(rows):
+        recs = records(pa[r]) + records(pb[r])
+        offs = [0] * pa.shape[1] + [half] * pb.shape[1]
+        mm, idx, tot = combine(recs, offs)
+        assert mm == m[r] and idx == t[r]
+        assert tot == pytest.approx(S[r], rel=1e-5)
+
+
+def test_workspace_needs_no_initialisation_and_is_reusable_across_shapes():
+    """One workspace, full of garbage at first, serves calls of different shapes back to back."""
+    rng = np.random.default_rng(41)
+    shapes = [(5, 3, 9000, "bf16"), (2, 7, 40000, "f32"), (9, 1, 3000, "bf16"), (5, 3, 9000, "bf16")]
+    need = max(csd.csd_verify_workspace_bytes(B, k, V, 0 if dt == "f32" else 1) for B, k, V, dt in shapes)
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")      # garbage
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    for rep in range(3):
+        for B, k, V, dt in shapes:
+            z = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+            if dt == "bf16":
+                z = f32_to_bf16_bits(z).reshape(B, k + 1, V)
+            am = np.stack([O.row_stats(z)[1]])[0][:, :k]
+            draft = np.where(rng.random((B, k)) < 0.5, am, rng.integers(0, 64, size=(B, k))).astype(np.int32)
+            bf = csd.VerifyBuffers.allocate(B, k, V, 0 if dt == "f32" else 1)
+            bf.workspace = ws
+            csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), 0.05, 1, ocm, buffers=bf)
+            torch.cuda.synchronize()
+            res = orc.verify_step(z, draft, tau=np.float32(0.05), lam=1)
+            compare_step(res, bf, "shape %r rep %d" % ((B, k, V, dt), rep))
+    compare_table(ocm, orc)
