@@ -7,11 +7,20 @@ memory updates.  Logits are synthetic (seeded generator, see gen/), already resi
 replayed from a ring of distinct steps larger than the last-level cache (>= 1 GiB, >= 4 steps) so
 that every step's rows come from HBM.
 
-Prints ONE JSON line: whole-path throughput in verified positions (rows) per second, the
-verify kernel's achieved HBM bandwidth against the 8 TB/s peak (timed live with events on the
-launch stream over the timed region; one launch per step), and the CPU oracle's rate on the host cores.
+Prints ONE JSON line: whole-path throughput in verified positions (rows) per second; the achieved HBM
+bandwidth of the dominant kernel (the streaming pass, row_partials_kernel) against the 8 TB/s peak, from
+its average launch duration measured with events on the launch stream while it is replayed over the same
+ring in the launch shape csd_verify uses; and the CPU oracle's rate on the host cores.
+
+Two more modes serve the hardware-counter runs (rocprofv3 --pmc) behind "roofline.traffic":
+  --pmc-run            a short run: a few csd_verify steps plus plain device-to-device copies of known
+                       size, whose counter readings calibrate the counter unit
+  --ingest-pmc F W     read the counter CSVs of a FETCH_SIZE run (F) and a WRITE_SIZE run (W) of --pmc-run
+                       and write profiles/traffic_row_partials.json (bytes per launch, kernel fingerprint)
 """
 import argparse
+import csv
+import glob
 import hashlib
 import json
 import math
@@ -24,16 +33,64 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak, GB/s
+STREAM_KERNEL = "row_partials_kernel"
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_row_partials.json")
+COPY_BYTES = 1 << 30           # the calibration copy moves 1 GiB in and 1 GiB out
 
 
 def kernel_fingerprint() -> str:
-    """Hash of the row-stream kernel's source and build flags: stored counter readings apply to one version only."""
+    """Hash of the streaming kernel's source and build flags: stored counter readings apply to one version only."""
     h = hashlib.sha256()
     for rel in ("paper_2604_13634_amd/csrc/csd_verify.hip", "paper_2604_13634_amd/csrc/csd_device.h",
                 "paper_2604_13634_amd/csrc/csd_internal.h", "paper_2604_13634_amd/build.py"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
+
+
+def read_counter(path: str, counter: str):
+    """{kernel name: [values per dispatch]} of one counter from rocprofv3's counter_collection CSV(s) under `path`."""
+    files = [path] if os.path.isfile(path) else glob.glob(os.path.join(path, "**", "*counter_collection.csv"), recursive=True)
+    out = {}
+    for fn in files:
+        with open(fn, newline="") as f:
+            for row in csv.DictReader(f):
+                if row.get("Counter_Name") != counter:
+                    continue
+                out.setdefault(row["Kernel_Name"], []).append(float(row["Counter_Value"]))
+    return out
+
+
+def ingest_pmc(fetch_path: str, write_path: str, workload: str) -> int:
+    """Scale FETCH_SIZE / WRITE_SIZE of the streaming kernel by what the same counters read for the 1 GiB copy."""
+    rec = {}
+    if os.path.exists(TRAFFIC_FILE):
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    ent = {"kernel": STREAM_KERNEL, "kernel_fingerprint": kernel_fingerprint(), "copy_bytes_each_way": COPY_BYTES}
+    total = 0.0
+    for name, path in (("FETCH_SIZE", fetch_path), ("WRITE_SIZE", write_path)):
+        per_kernel = read_counter(path, name)
+        stream = [v for k, vals in per_kernel.items() if STREAM_KERNEL in k for v in vals]
+        # the calibration copies are the only launches of torch's elementwise copy kernel on 2^30 bytes:
+        # take the kernel whose name mentions a copy and whose reading is largest
+        copies = [v for k, vals in per_kernel.items() if "copy" in k.lower() or "Copy" in k for v in vals]
+        if not stream or not copies:
+            print("bench.py: no %s readings for the streaming kernel or the copy in %s" % (name, path), file=sys.stderr)
+            return 1
+        copy_read = max(copies)
+        unit = COPY_BYTES / copy_read                      # bytes per counter unit on this machine
+        mean = sum(stream) / len(stream)
+        ent[name] = {"stream_mean_reading": mean, "stream_launches": len(stream), "copy_reading": copy_read,
+                     "bytes_per_unit": unit, "bytes_per_launch": mean * unit}
+        total += mean * unit
+    ent["hbm_bytes_per_launch"] = total
+    rec[workload] = ent
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(rec, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print(json.dumps(ent))
+    return 0
 
 
 def main() -> int:
@@ -45,25 +102,32 @@ def main() -> int:
     ap.add_argument("--ring-bytes", type=float, default=float(1 << 30), help="minimum bytes of distinct logits in the ring")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--pmc-run", action="store_true", help="short run for rocprofv3 --pmc (see module docstring)")
+    ap.add_argument("--ingest-pmc", nargs=2, metavar=("FETCH", "WRITE"))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
         return 2
 
+    from gen import CONFIGS, Workload
+    cfg = CONFIGS[args.config]
+    if args.ingest_pmc:
+        return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name)
+
     import numpy as np
     import torch
 
-    from gen import CONFIGS, Workload
     from paper_2604_13634_amd import binding as csd
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from parity_util import to_device_logits
 
     torch.cuda.set_device(0)
-    cfg = CONFIGS[args.config]
     w = Workload(cfg)
     rows = cfg.rows
     n_ring = max(4, int(math.ceil(args.ring_bytes / cfg.bytes_per_step)))
+    if args.pmc_run:
+        n_ring, args.steps, args.warmup = 4, 8, 2
 
     # ---- inputs: generated on the host, copied to HBM before anything is timed
     t_gen = time.perf_counter()
@@ -95,15 +159,27 @@ def main() -> int:
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ocm, e0.elapsed_time(e1) / steps
 
-    # ---- the headline: whole hot path (one kernel launch per step), memory updates applied
-    elapsed, ocm, fused_ms = timed_steps(csd.CSD_APPLY_UPDATES, args.steps, args.warmup)
+    if args.pmc_run:
+        timed_steps(csd.CSD_APPLY_UPDATES, args.steps, args.warmup)
+        src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
+        src.random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("pmc-run done: %d csd_verify steps of %s, 3 copies of %d bytes" % (args.steps + args.warmup, cfg.name, COPY_BYTES))
+        return 0
+
+    # ---- the headline: whole hot path (two launches per step), memory updates applied
+    elapsed, ocm, step_ms_events = timed_steps(csd.CSD_APPLY_UPDATES, args.steps, args.warmup)
     ms_per_step = elapsed / args.steps * 1e3
     value = rows * args.steps / elapsed
     accept_rate = float(bf.accept_len.float().mean().item()) / max(cfg.k, 1)
     status = bf.status.cpu().numpy().view(np.uint32).tolist()
     elapsed_noupd, _, _ = timed_steps(0, args.steps, args.warmup)
 
-    # ---- for reference: the streaming pass alone (csd_row_partials), same ring, same launch shape
+    # ---- the dominant kernel: the streaming pass (csd_row_partials launches exactly the kernel and grid that
+    # csd_verify launches first), same ring, events on the launch stream
     part = csd.csd_row_partials(ring_z[0])
     for i in range(args.warmup):
         csd.csd_row_partials(ring_z[i % n_ring], part)
@@ -115,13 +191,12 @@ def main() -> int:
     ev1.record()
     torch.cuda.synchronize()
     k_ms = ev0.elapsed_time(ev1) / args.steps
-    alg_bytes = rows * cfg.V * cfg.itemsize            # every logit read once; outputs are a few KB
-    achieved = alg_bytes / (fused_ms * 1e-3) / 1e9      # the fused verify kernel, timed over the timed region
+    alg_bytes = rows * cfg.V * cfg.itemsize            # every logit read once; partials and outputs are a few KB
+    achieved = alg_bytes / (k_ms * 1e-3) / 1e9
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_row_stream.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
+    if os.path.exists(TRAFFIC_FILE):
+        with open(TRAFFIC_FILE) as f:
             rec = json.load(f)
         ent = rec.get(cfg.name)
         if ent and ent.get("kernel_fingerprint") == kernel_fingerprint():
@@ -147,17 +222,16 @@ def main() -> int:
             "ring_steps": n_ring, "ring_bytes": n_ring * cfg.bytes_per_step,
             "positions_per_s_without_ocm_updates": rows * args.steps / elapsed_noupd,
             "ms_per_step_without_ocm_updates": elapsed_noupd / args.steps * 1e3,
+            "ms_per_step_by_stream_events": step_ms_events,
             "whole_path_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
             "whole_path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "accept_rate_last_step": accept_rate, "status_counters": status,
             "input_generation_s": t_gen,
         },
         "roofline": {
-            "bound": "hbm", "kernel": "verify_kernel<%s, fused> (one launch per step)" % cfg.dtype, "achieved": achieved,
+            "bound": "hbm", "kernel": "%s<%s>" % (STREAM_KERNEL, cfg.dtype), "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-            "kernel_ms": fused_ms, "algorithmic_bytes_per_launch": alg_bytes,
-            "streaming_pass_alone": {"kernel_ms": k_ms, "GBps": alg_bytes / (k_ms * 1e-3) / 1e9,
-                                     "frac": alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "kernel_ms": k_ms, "algorithmic_bytes_per_launch": alg_bytes,
         },
     }
 

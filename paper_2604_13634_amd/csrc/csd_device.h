@@ -104,21 +104,78 @@ __device__ inline bool ocm_add(uint64_t *ocm, uint64_t capacity, uint64_t key, u
     return false;
 }
 
-// LDS pre-aggregation table: distinct keys of a batch of log entries with their summed weights.
-constexpr int kLdsSlots = 1024;                // >= 2 * entries aggregated at a time: never fills
-constexpr int kLdsBatch = kLdsSlots / 2;
+// ---- applying a list of (key, weight) entries to the table, one workgroup of kApplyThreads threads.
+// Entries are merged in an LDS hash table first, kApplyBatch at a time, so a skewed list costs one
+// compare-and-swap chain per DISTINCT pair; the distinct pairs are then compacted so that all of them
+// go to the table side by side (one round of global atomics per kApplyThreads distinct pairs) instead of
+// slot by slot.
+constexpr int kApplyThreads = 256;
+constexpr int kApplyBatch = 1024;                 // entries merged at a time
+constexpr int kApplySlots = 2 * kApplyBatch;      // LDS table never fills
+constexpr int kApplyPerThread = kApplyBatch / kApplyThreads;
 
-__device__ __forceinline__ void lds_aggregate(unsigned long long *lkey, unsigned long long *lcnt, uint64_t key, uint32_t w) {
-    uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) & (kLdsSlots - 1);
+struct ApplyLds {
+    unsigned long long key[kApplySlots];
+    unsigned long long cnt[kApplySlots];          // 64-bit: kApplyBatch weights of up to 2^24-1 do not wrap
+    unsigned long long ckey[kApplyBatch];         // compacted distinct pairs ...
+    unsigned long long ccnt[kApplyBatch];         // ... and their summed weights
+    unsigned int ndistinct;
+};
+
+__device__ __forceinline__ void lds_aggregate(ApplyLds &L, uint64_t key, uint32_t w) {
+    uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) & (kApplySlots - 1);
     for (;;) {
-        unsigned long long cur = lkey[i];
-        if (cur == CSD_OCM_EMPTY) cur = atomicCAS(&lkey[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
+        unsigned long long cur = L.key[i];
+        if (cur == CSD_OCM_EMPTY) cur = atomicCAS(&L.key[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
         if (cur == CSD_OCM_EMPTY || cur == key) {
-            atomicAdd(&lcnt[i], (unsigned long long)w);
+            atomicAdd(&L.cnt[i], (unsigned long long)w);
             return;
         }
-        i = (i + 1) & (kLdsSlots - 1);
+        i = (i + 1) & (kApplySlots - 1);
     }
+}
+
+// Entries [base, min(base + kApplyBatch, n)) of a list; fetch(e, key, w) reads entry e.  Called by every
+// thread of the workgroup (it contains barriers).  Entries with an empty key or zero weight are skipped.
+template <typename Fetch>
+__device__ __forceinline__ void block_apply_batch(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L,
+                                                  Fetch fetch, uint64_t base, uint64_t n) {
+    const int tid = threadIdx.x;
+    uint64_t key[kApplyPerThread];
+    uint32_t w[kApplyPerThread];
+#pragma unroll
+    for (int j = 0; j < kApplyPerThread; ++j) {     // all global reads first: their latencies overlap
+        const uint64_t e = base + (uint64_t)(j * kApplyThreads + tid);
+        key[j] = CSD_OCM_EMPTY;
+        w[j] = 0;
+        if (e < n) fetch(e, key[j], w[j]);
+    }
+    for (int i = tid; i < kApplySlots; i += kApplyThreads) {
+        L.key[i] = CSD_OCM_EMPTY;
+        L.cnt[i] = 0;
+    }
+    if (tid == 0) L.ndistinct = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kApplyPerThread; ++j)
+        if (key[j] != CSD_OCM_EMPTY && w[j] != 0) lds_aggregate(L, key[j], w[j]);
+    __syncthreads();
+    for (int i = tid; i < kApplySlots; i += kApplyThreads) {
+        const unsigned long long sk = L.key[i];
+        if (sk != CSD_OCM_EMPTY) {
+            const unsigned int pos = atomicAdd(&L.ndistinct, 1u);
+            L.ckey[pos] = sk;
+            L.ccnt[pos] = L.cnt[i];
+        }
+    }
+    __syncthreads();
+    const unsigned int nd = L.ndistinct;
+    for (unsigned int i = tid; i < nd; i += kApplyThreads) {
+        const unsigned long long sum = L.ccnt[i];
+        const uint32_t ww = (sum > CSD_OCM_COUNT_MAX) ? CSD_OCM_COUNT_MAX : (uint32_t)sum;
+        if (!ocm_add(ocm, capacity, L.ckey[i], ww) && status) atomicAdd(&status[CSD_STATUS_DROPPED], ww);
+    }
+    __syncthreads();                                // the next batch reuses the LDS arrays
 }
 
 __device__ __forceinline__ float load_logit(const void *logits, int dtype, int64_t elem) {

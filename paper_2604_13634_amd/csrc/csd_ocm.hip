@@ -5,39 +5,19 @@
 namespace csd {
 namespace {
 
-constexpr int kUpdThreads = 256;
-
-// Each workgroup merges duplicate keys of kLdsBatch entries in LDS, then issues one compare-and-swap
+// Each workgroup takes kApplyBatch entries: merges duplicate keys in LDS, then issues one compare-and-swap
 // chain per distinct key, so a skewed stream does not serialise on a handful of global slots.
-__global__ __launch_bounds__(kUpdThreads) void ocm_update_kernel(uint64_t *ocm, uint64_t capacity,
-                                                                 const uint64_t *__restrict__ keys,
-                                                                 const uint32_t *__restrict__ weights, uint64_t n,
-                                                                 uint32_t *status) {
-    __shared__ unsigned long long lkey[kLdsSlots];
-    __shared__ unsigned long long lcnt[kLdsSlots];   // 64-bit: kLdsBatch weights of up to 2^24-1 do not wrap
-    for (int i = threadIdx.x; i < kLdsSlots; i += kUpdThreads) {
-        lkey[i] = CSD_OCM_EMPTY;
-        lcnt[i] = 0;
-    }
-    __syncthreads();
-    const uint64_t base = (uint64_t)blockIdx.x * kLdsBatch;
-    for (int j = threadIdx.x; j < kLdsBatch; j += kUpdThreads) {
-        const uint64_t e = base + j;
-        if (e >= n) break;
-        const uint64_t key = keys[e] & CSD_OCM_KEY_MASK;
-        uint32_t w = weights ? weights[e] : 1u;
-        if (key == CSD_OCM_EMPTY || w == 0) continue;
+__global__ __launch_bounds__(kApplyThreads) void ocm_update_kernel(uint64_t *ocm, uint64_t capacity,
+                                                                   const uint64_t *__restrict__ keys,
+                                                                   const uint32_t *__restrict__ weights, uint64_t n,
+                                                                   uint32_t *status) {
+    __shared__ ApplyLds lds;
+    auto fetch = [&](uint64_t e, uint64_t &key, uint32_t &w) {
+        key = keys[e] & CSD_OCM_KEY_MASK;
+        w = weights ? weights[e] : 1u;
         if (w > CSD_OCM_COUNT_MAX) w = CSD_OCM_COUNT_MAX;
-        lds_aggregate(lkey, lcnt, key, w);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kLdsSlots; i += kUpdThreads) {
-        const unsigned long long key = lkey[i];
-        if (key == CSD_OCM_EMPTY) continue;
-        const unsigned long long sum = lcnt[i];
-        const uint32_t w = (sum > CSD_OCM_COUNT_MAX) ? CSD_OCM_COUNT_MAX : (uint32_t)sum;
-        if (!ocm_add(ocm, capacity, key, w) && status) atomicAdd(&status[CSD_STATUS_DROPPED], w);
-    }
+    };
+    block_apply_batch(ocm, capacity, status, lds, fetch, (uint64_t)blockIdx.x * kApplyBatch, n);
 }
 
 __global__ void ocm_reset_kernel(uint64_t *ocm, uint64_t capacity) {
@@ -59,8 +39,8 @@ __global__ void ocm_lookup_kernel(const uint64_t *__restrict__ ocm, uint64_t cap
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const uint64_t blocks = (n + kLdsBatch - 1) / kLdsBatch;
-    hipLaunchKernelGGL(ocm_update_kernel, dim3((unsigned)blocks), dim3(kUpdThreads), 0, stream, ocm, capacity, keys, weights, n,
+    const uint64_t blocks = (n + kApplyBatch - 1) / kApplyBatch;
+    hipLaunchKernelGGL(ocm_update_kernel, dim3((unsigned)blocks), dim3(kApplyThreads), 0, stream, ocm, capacity, keys, weights, n,
                        status);
     return hipGetLastError();
 }

@@ -21,16 +21,17 @@
 //   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
 //   c itself is carried exactly into the combine.
 //
-// Kernel 2 - finish (finish_kernel), one wave per sequence: combine the row partials (normaliser in
-// double), draft-token ratio and probability (Eq. 3), memory lookup then gate (Algorithm 1),
-// accepted-prefix scan by ballot, emitted token, and the list of divergences to count.  Each wave then
-// takes a ticket on the batch; the wave that draws the last ticket knows that every lookup of the step
-// has been made and applies the step's increments, so all lookups read the table as it stood when the
-// step began.  No wave waits for another.  The log handed from the sequence waves to the updating wave
-// is written with agent-scope atomic stores (write-through to where the eight XCDs' L2s agree) and read
-// back with agent-scope atomic loads; a writer waits for its stores to be acknowledged before it draws
-// its ticket, itself an agent-scope atomic add.  (A release/acquire fence pair would do the same job by
-// writing back and invalidating a whole L2 per wave, which measured ten times the streaming pass.)
+// Kernel 2 - finish (finish_kernel), one wave per sequence, four sequences per workgroup: combine the row
+// partials (normaliser in double), draft-token ratio and probability (Eq. 3), memory lookup then gate
+// (Algorithm 1), accepted-prefix scan by ballot, emitted token, and the list of divergences to count.
+// Each workgroup then takes a ticket on the batch; the workgroup that draws the last ticket knows that
+// every lookup of the step has been made and applies the step's increments with all its threads, so all
+// lookups read the table as it stood when the step began.  No workgroup waits for another.  The log
+// handed from the sequence waves to the updating workgroup is written with agent-scope atomic stores
+// (write-through to where the eight XCDs' L2s agree) and read back with agent-scope atomic loads; the
+// writers' stores are acknowledged before the workgroup barrier that precedes the ticket, itself an
+// agent-scope atomic add.  (A release/acquire fence pair would do the same job by writing back and
+// invalidating a whole L2 per wave, which measured ten times the streaming pass.)
 #include "csd_device.h"
 
 namespace csd {
@@ -102,19 +103,20 @@ __device__ __forceinline__ void xwg_store64(uint64_t *p, uint64_t v) {
 __device__ __forceinline__ uint64_t xwg_load64(const uint64_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// One atomic ticket: true in every lane of the wave that drew the last of `total` tickets.
-// Before the ticket the wave waits until its earlier stores are acknowledged (workgroup-scope release =
-// s_waitcnt, and a compiler barrier); after it a workgroup-scope acquire keeps later loads from moving up.
-__device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int lane) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    int last = 0;
-    if (lane == 0) {
+// One atomic ticket per workgroup: true in every thread of the workgroup that drew the last of `total`
+// tickets.  Every wave first waits until its own vector-memory operations are acknowledged
+// (s_waitcnt vmcnt(0): on gfx9 the counter covers stores, and a write-through store is acknowledged once
+// it is visible at agent scope) - a workgroup barrier alone does not wait for them.  The second barrier
+// hands the verdict round; the reads of the log depend on it, so they cannot be issued early.
+__device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int *verdict) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0); expcnt and lgkmcnt left alone
+    __syncthreads();
+    if (threadIdx.x == 0) {
         const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = (old == total - 1);
+        *verdict = (old == total - 1);
     }
-    last = __builtin_amdgcn_readfirstlane(last);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    return last != 0;
+    __syncthreads();
+    return *verdict != 0;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -352,47 +354,6 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     }
 }
 
-// ---------------------------------------------------------------------------------------------------
-// Phase 3: one wave applies the step's log (n entries) to the table.  Duplicates are merged in an LDS
-// table first, so a skewed step costs one compare-and-swap chain per distinct pair.
-__device__ __forceinline__ void wave_apply_log(const EpilogueArgs &a, unsigned long long *lkey, unsigned long long *lcnt,
-                                               int lane) {
-    const int64_t n = (int64_t)a.B * a.k;
-    if (n <= kWaveSize) {                           // tiny step: no aggregation
-        const uint64_t key = (lane < n) ? (xwg_load64(&a.rej_log[lane]) & CSD_OCM_KEY_MASK) : CSD_OCM_EMPTY;
-        if (key != CSD_OCM_EMPTY && !ocm_add(a.ocm, a.capacity, key, 1u) && a.status)
-            atomicAdd(&a.status[CSD_STATUS_DROPPED], 1u);
-        return;
-    }
-    for (int64_t base = 0; base < n; base += kLdsBatch) {
-        for (int i = lane; i < kLdsSlots; i += kWaveSize) {
-            lkey[i] = CSD_OCM_EMPTY;
-            lcnt[i] = 0;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        uint64_t ent[kLdsBatch / kWaveSize];         // all loads first, then the LDS work
-#pragma unroll
-        for (int j = 0; j < kLdsBatch / kWaveSize; ++j) {
-            const int64_t e = base + j * kWaveSize + lane;
-            ent[j] = (e < n) ? (xwg_load64(&a.rej_log[e]) & CSD_OCM_KEY_MASK) : CSD_OCM_EMPTY;
-        }
-#pragma unroll
-        for (int j = 0; j < kLdsBatch / kWaveSize; ++j)
-            if (ent[j] != CSD_OCM_EMPTY) lds_aggregate(lkey, lcnt, ent[j], 1u);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        for (int i = lane; i < kLdsSlots; i += kWaveSize) {
-            const unsigned long long key = lkey[i];
-            if (key == CSD_OCM_EMPTY) continue;
-            const uint32_t w = (uint32_t)lcnt[i];
-            if (!ocm_add(a.ocm, a.capacity, key, w) && a.status) atomicAdd(&a.status[CSD_STATUS_DROPPED], w);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
-}
-
 template <int DT>
 __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kernel(const char *__restrict__ logits,
                                                                                   int64_t row_pitch_bytes, int V, int nsplit,
@@ -410,18 +371,24 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kerne
     if (lane == 0) partials[((int64_t)row * nsplit + split) * kStreamWaves + wave] = out;   // one 16-byte store
 }
 
-constexpr int kFinishWaves = 4;
+constexpr int kFinishWaves = kApplyThreads / kWaveSize;
 
-__global__ __launch_bounds__(kFinishWaves *kWaveSize) void finish_kernel(EpilogueArgs a) {
-    __shared__ unsigned long long lkey[kLdsSlots];
-    __shared__ unsigned long long lcnt[kLdsSlots];
+__global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
+    __shared__ ApplyLds lds;
+    __shared__ int verdict;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (b >= a.B) return;                           // whole wave leaves together
-    sequence_epilogue(a, b, lane);
+    if (b < a.B) sequence_epilogue(a, b, lane);      // wave-uniform: a wave takes a sequence or none
     if (!a.apply_updates) return;
-    if (!take_last_ticket(a.batch_ticket, (uint32_t)a.B, lane)) return;
-    wave_apply_log(a, lkey, lcnt, lane);            // every lookup of the step has been made
+    if (!take_last_ticket(a.batch_ticket, gridDim.x, &verdict)) return;
+    // Phase 3: every lookup of the step has been made; this workgroup applies the step's log.
+    const uint64_t n = (uint64_t)a.B * (uint64_t)a.k;
+    auto fetch = [&](uint64_t e, uint64_t &key, uint32_t &w) {
+        key = xwg_load64(&a.rej_log[e]) & CSD_OCM_KEY_MASK;
+        w = 1u;
+    };
+    for (uint64_t base = 0; base < n; base += kApplyBatch)
+        block_apply_batch(a.ocm, a.capacity, a.status, lds, fetch, base, n);
 }
 
 }  // namespace

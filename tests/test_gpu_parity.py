@@ -217,6 +217,25 @@ def test_deferred_updates_through_rejection_log():
     compare_table(ocm_b, orc)
 
 
+@pytest.mark.parametrize("B", [300, 700, 2200])
+def test_large_batches_update_paths(B):
+    """B*k of 1200 and 2800 (several merge batches inside the finish kernel) and 8800 (beyond what the
+    finish kernel applies itself: the separate update launch), on the skewed pair stream."""
+    w = Workload(CONFIGS[4], V=1030, B=B)
+    cfg = w.cfg
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    bf = None
+    for step in range(5):
+        z, draft = w.step(step)
+        bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), cfg.tau, cfg.lam, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=cfg.lam)
+        compare_step(res, bf, "B=%d step %d" % (B, step))
+        compare_table(ocm, orc, "B=%d step %d" % (B, step))
+    assert int(bf.status[csd.CSD_STATUS_COUNTED]) == sum(orc.T.values())
+
+
 def test_bad_draft_ids_are_divergences_never_counted():
     rng = np.random.default_rng(4)
     B, k, V = 8, 4, 1000
