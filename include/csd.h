@@ -96,8 +96,8 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  * Inputs
  *   logits      [B][k+1][V] target logits, row-major, dtype CSD_DTYPE_F32 (float) or CSD_DTYPE_BF16
  *               (bfloat16 bit patterns).  Row r = b*(k+1)+i starts at element r*row_stride.  Values
- *               are finite or -inf with at least one finite value per row, |z| < 1e38; NaN/+inf are
- *               undefined behaviour of the result (never a fault).  Base and row pitch must be
+ *               are finite with |z| <= 2^29 (about 5.4e8), or -inf, with at least one finite value
+ *               per row; NaN, +inf and larger magnitudes give undefined results (never a fault).  Base and row pitch must be
  *               16-byte aligned.  Rows 0..k-1 of a sequence belong to its draft positions, row k is
  *               the bonus row.
  *   row_stride  elements between consecutive rows, >= V.

@@ -19,7 +19,8 @@
 //   when some lane's maximum climbs more than kRescaleGap above the reference - at the first tile, then
 //   almost never - so the steady-state loop is unpack, max3, fma, v_exp_f32, add and one compare per
 //   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
-//   c itself is carried exactly into the combine.
+//   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
+//   2^d with |d| <= ulp(c)/2: this is why logits are limited to |z| <= 2^29 (d <= 32, sums stay in range).
 //
 // Kernel 2 - finish (finish_kernel), one wave per sequence, four sequences per workgroup: combine the row
 // partials (normaliser in double), draft-token ratio and probability (Eq. 3), memory lookup then gate
@@ -271,22 +272,32 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     const int grow = lane / G, gs = lane & (G - 1);
     const bool active = grow < K1;
     const RowPartial *pp = a.partials + ((int64_t)b * K1 + (active ? grow : 0)) * P;
-    float m = -INFINITY;
-    for (int j = gs; j < P; j += G) m = fmaxf(m, pp[j].m);
-    float gm = m;
-    for (int x = 1; x < G; x <<= 1) gm = fmaxf(gm, xchg_f(gm, x));
-    const double mref = (double)gm * kLog2eD;
+    // one pass: running maximum gm, its lowest token id t, and S kept relative to gm
+    float gm = -INFINITY;
     int t = 0x7fffffff;
     double S = 0.0;
     for (int j = gs; j < P; j += G) {
         const RowPartial q = pp[j];
-        if (q.m == gm && q.idx < t) t = q.idx;
-        if (q.s != 0.f) S += (double)q.s * exp2((double)q.cref - mref);
+        if (q.m > gm || (q.m == gm && q.idx < t)) t = q.idx;
+        if (q.s != 0.f) {                                       // then q.m is finite
+            const float mn = fmaxf(gm, q.m);
+            const double ref = (double)mn * kLog2eD;            // exact: two 24-bit significands
+            const double keep = (S != 0.0) ? S * exp2((double)gm * kLog2eD - ref) : 0.0;
+            S = keep + (double)q.s * exp2((double)q.cref - ref);
+        }
+        gm = fmaxf(gm, q.m);
     }
     for (int x = 1; x < G; x <<= 1) {
-        S += xchg_d(S, x);
+        const float om = xchg_f(gm, x);
         const int ot = xchg_i(t, x);
-        t = ot < t ? ot : t;
+        const double oS = xchg_d(S, x);
+        if (om > gm || (om == gm && ot < t)) t = ot;
+        const float mn = fmaxf(gm, om);
+        const double ref = (double)mn * kLog2eD;
+        const double mine = (S != 0.0) ? S * exp2((double)gm * kLog2eD - ref) : 0.0;
+        const double theirs = (oS != 0.0) ? oS * exp2((double)om * kLog2eD - ref) : 0.0;
+        S = mine + theirs;
+        gm = mn;
     }
     if (active && gs == 0) {
         const int64_t row = (int64_t)b * K1 + grow;

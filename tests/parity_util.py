@@ -39,9 +39,10 @@ def to_device_logits(z: np.ndarray) -> torch.Tensor:
 
 def assert_close(gpu: np.ndarray, ref: np.ndarray, what: str):
     gpu = gpu.astype(np.float64)
+    assert np.all(np.isfinite(gpu)), "%s: non-finite value from the GPU" % what
     err = np.abs(gpu - ref)
     tol = RTOL * np.abs(ref) + ATOL
-    bad = err > tol
+    bad = ~(err <= tol)                       # a NaN on either side fails
     if bad.any():
         i = int(np.argmax(err - tol))
         raise AssertionError("%s: %d values beyond 1e-5 relative; worst gpu=%r oracle=%r" %
