@@ -73,7 +73,8 @@ extern "C" {
 #define CSD_STATUS_BAD_DRAFT 1 /* processed draft ids outside [0, V)                             */
 #define CSD_STATUS_RESCUED 2   /* positions kept by the memory + gate although draft != t*       */
 #define CSD_STATUS_COUNTED 3   /* divergences handed to UpdateMemory                             */
-#define CSD_STATUS_WORDS 4
+#define CSD_STATUS_ACCEPTED 4   /* draft tokens kept, summed over sequences (acceptance rate = this / (B*k) per call) */
+#define CSD_STATUS_WORDS 8     /* words 5..7 are reserved and left untouched */
 
 /* pos_flags bits, per draft position; 0 for positions after the stop */
 #define CSD_POS_MATCH 1u     /* draft == t*                                        */
@@ -158,6 +159,26 @@ int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream);
  */
 int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys, uint32_t *counts, uint64_t n,
                    void *stream);
+
+/*
+ * csd_ocm_merge - T_dst[pair] += T_src[pair] for every pair held by src (counts saturate).  The life cycle
+ * of the memory beyond a single run ("prior calibration" is a one-time offline product that later runs
+ * start from): growing a table (reset a larger one, merge the old one into it = rehash), combining
+ * memories calibrated on different corpora, folding per-device replicas.  dst and src must not overlap.
+ * A pair that finds no free slot in dst is dropped and its count added to status[CSD_STATUS_DROPPED].
+ */
+int csd_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uint64_t src_capacity, uint32_t *status,
+                  void *stream);
+
+/*
+ * csd_ocm_export - the table as a compact list, layout-independent (what a checkpoint or an exchange
+ * between devices carries): keys_out[j] = CSD_OCM_KEY(draft, target), counts_out[j] = its count, for the
+ * n pairs the table holds, in unspecified order.  *n_out (device, uint64) receives n; when n exceeds
+ * max_entries only max_entries pairs are written.  keys_out / counts_out may be NULL with max_entries == 0
+ * (count only).  The list can be fed back through csd_ocm_update(keys, counts).
+ */
+int csd_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *keys_out, uint32_t *counts_out, uint64_t max_entries,
+                   uint64_t *n_out, void *stream);
 
 /*
  * Row partials: the streaming pass over the logits on its own (the p_{1:gamma+1}(.) statistics of

@@ -157,6 +157,15 @@ class CSDOracle:
                 self.T[key] = 0
             self.T[key] = min(self.T[key] + w, COUNT_MAX)
 
+    # Memory life cycle around runs (the calibrated prior is an offline product that later runs start from):
+    # folding another memory in, and the memory as a plain list of (pair, count).
+    def ocm_merge(self, other: "CSDOracle") -> None:
+        for key, cnt in other.T.items():
+            self.ocm_update([key], [cnt])
+
+    def ocm_export(self) -> Dict[Tuple[int, int], int]:
+        return dict(self.T)
+
     def verify_step(self, z: np.ndarray, draft: np.ndarray, tau: float, lam: int, apply_updates: bool = True,
                     use_ocm: bool = True, threads: int = 1) -> StepResult:
         """One decode step for a batch.  z: [B][k+1][V] stored logits, draft: [B][k] token ids."""

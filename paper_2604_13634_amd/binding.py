@@ -26,8 +26,8 @@ CSD_OCM_KEY_BITS = 40
 CSD_OCM_KEY_MASK = (1 << 40) - 1
 CSD_OCM_EMPTY = (1 << 40) - 1
 CSD_OCM_COUNT_MAX = (1 << 24) - 1
-CSD_STATUS_DROPPED, CSD_STATUS_BAD_DRAFT, CSD_STATUS_RESCUED, CSD_STATUS_COUNTED = 0, 1, 2, 3
-CSD_STATUS_WORDS = 4
+CSD_STATUS_DROPPED, CSD_STATUS_BAD_DRAFT, CSD_STATUS_RESCUED, CSD_STATUS_COUNTED, CSD_STATUS_ACCEPTED = 0, 1, 2, 3, 4
+CSD_STATUS_WORDS = 8
 CSD_POS_MATCH, CSD_POS_FREQ, CSD_POS_SAFE, CSD_POS_ACCEPTED, CSD_POS_COUNTED = 1, 2, 4, 8, 16
 
 
@@ -62,6 +62,10 @@ def load_library() -> ctypes.CDLL:
     lib.csd_ocm_reset.argtypes = [vp, u64, vp]
     lib.csd_ocm_lookup.restype = i32
     lib.csd_ocm_lookup.argtypes = [vp, u64, vp, vp, u64, vp]
+    lib.csd_ocm_merge.restype = i32
+    lib.csd_ocm_merge.argtypes = [vp, u64, vp, u64, vp, vp]
+    lib.csd_ocm_export.restype = i32
+    lib.csd_ocm_export.argtypes = [vp, u64, vp, vp, u64, vp, vp]
     lib.csd_row_partials_per_row.restype = i32
     lib.csd_row_partials_per_row.argtypes = [i32, i32, i32]
     lib.csd_row_partials.restype = i32
@@ -202,6 +206,28 @@ def csd_ocm_lookup(ocm: torch.Tensor, keys: torch.Tensor, stream=None) -> torch.
     if rc != CSD_OK:
         raise CsdError(rc, "csd_ocm_lookup")
     return counts
+
+
+def csd_ocm_merge(dst: torch.Tensor, src: torch.Tensor, status: Optional[torch.Tensor] = None, stream=None) -> None:
+    """T_dst[pair] += T_src[pair] for every pair of src (both int64 tables of power-of-two size)."""
+    rc = load_library().csd_ocm_merge(_ptr(dst), dst.numel(), _ptr(src), src.numel(), _ptr(status), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_ocm_merge")
+
+
+def csd_ocm_export(ocm: torch.Tensor, max_entries: Optional[int] = None, stream=None):
+    """Enqueue the export; returns (keys int64 [max_entries], counts int32 [max_entries], n int64 [1]) on the device.
+    Entries beyond n are unwritten."""
+    if max_entries is None:
+        max_entries = ocm.numel()
+    keys = torch.empty((max_entries,), dtype=torch.int64, device=ocm.device)
+    counts = torch.empty((max_entries,), dtype=torch.int32, device=ocm.device)
+    n = torch.empty((1,), dtype=torch.int64, device=ocm.device)
+    rc = load_library().csd_ocm_export(_ptr(ocm), ocm.numel(), _ptr(keys) if max_entries else None,
+                                       _ptr(counts) if max_entries else None, max_entries, _ptr(n), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_ocm_export")
+    return keys, counts, n
 
 
 def csd_row_partials_per_row(rows: int, V: int, dtype: int) -> int:

@@ -128,6 +128,24 @@ int csd_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys,
     return launch_ocm_lookup(ocm, capacity, keys, counts, n, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
+int csd_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uint64_t src_capacity, uint32_t *status,
+                  void *stream) {
+    if (!dst || !src || !is_pow2(dst_capacity) || !is_pow2(src_capacity)) return CSD_EINVAL;
+    if (!aligned(dst, 8) || !aligned(src, 8) || !aligned(status, 4)) return CSD_EALIGN;
+    const uintptr_t d0 = (uintptr_t)dst, d1 = d0 + dst_capacity * 8, s0 = (uintptr_t)src, s1 = s0 + src_capacity * 8;
+    if (d0 < s1 && s0 < d1) return CSD_EINVAL;   // overlapping tables
+    return launch_ocm_merge(dst, dst_capacity, src, src_capacity, status, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+int csd_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *keys_out, uint32_t *counts_out, uint64_t max_entries,
+                   uint64_t *n_out, void *stream) {
+    if (!ocm || !is_pow2(capacity) || !n_out) return CSD_EINVAL;
+    if (max_entries > 0 && (!keys_out || !counts_out)) return CSD_EINVAL;
+    if (!aligned(ocm, 8) || !aligned(keys_out, 8) || !aligned(counts_out, 4) || !aligned(n_out, 8)) return CSD_EALIGN;
+    return launch_ocm_export(ocm, capacity, keys_out, counts_out, max_entries, n_out, (hipStream_t)stream) == hipSuccess
+               ? CSD_OK : CSD_EHIP;
+}
+
 int csd_row_partials_per_row(int rows, int V, int dtype) {
     if (rows < 0 || !shape_ok(0, 0, V, dtype) || rows > (1 << 24)) return 0;
     return make_stream_plan(rows, V, dtype).partials_per_row;

@@ -76,6 +76,10 @@ hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream);
 hipError_t launch_ocm_reset(uint64_t *ocm, uint64_t capacity, hipStream_t stream);
+hipError_t launch_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uint64_t src_capacity,
+                            uint32_t *status, hipStream_t stream);
+hipError_t launch_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *keys_out, uint32_t *counts_out,
+                             uint64_t max_entries, uint64_t *n_out, hipStream_t stream);
 hipError_t launch_ocm_lookup(const uint64_t *ocm, uint64_t capacity, const uint64_t *keys, uint32_t *counts, uint64_t n,
                              hipStream_t stream);
 

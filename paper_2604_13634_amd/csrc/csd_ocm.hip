@@ -34,7 +34,70 @@ __global__ void ocm_lookup_kernel(const uint64_t *__restrict__ ocm, uint64_t cap
     }
 }
 
+// every pair of src goes into dst with its count; keys of one table are distinct, so no merging first
+__global__ void ocm_merge_kernel(uint64_t *dst, uint64_t dst_capacity, const uint64_t *__restrict__ src,
+                                 uint64_t src_capacity, uint32_t *status) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < src_capacity; i += stride) {
+        const uint64_t s = src[i];
+        const uint64_t key = slot_key(s);
+        const uint32_t w = slot_count(s);
+        if (key == CSD_OCM_EMPTY || w == 0) continue;
+        if (!ocm_add(dst, dst_capacity, key, w) && status) atomicAdd(&status[CSD_STATUS_DROPPED], w);
+    }
+}
+
+__global__ void zero_u64_kernel(unsigned long long *p) { *p = 0; }
+
+// compaction: one atomic per wave reserves room for the wave's occupied slots
+__global__ void ocm_export_kernel(const uint64_t *__restrict__ ocm, uint64_t capacity, uint64_t *__restrict__ keys_out,
+                                  uint32_t *__restrict__ counts_out, uint64_t max_entries, unsigned long long *n_out) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t first = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    // whole waves iterate together (the bound is rounded up to the wave), so the ballot sees all 64 lanes
+    for (uint64_t base = first - lane; base < capacity; base += stride) {
+        const uint64_t i = base + lane;
+        const uint64_t s = (i < capacity) ? ocm[i] : CSD_OCM_EMPTY;
+        const bool used = slot_key(s) != CSD_OCM_EMPTY;
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(used);
+        if (mask == 0) continue;
+        unsigned long long start = 0;
+        if (lane == 0) start = atomicAdd(n_out, (unsigned long long)__builtin_popcountll(mask));
+        start = ((unsigned long long)__builtin_amdgcn_readfirstlane((int)(start >> 32)) << 32) |
+                (unsigned int)__builtin_amdgcn_readfirstlane((int)(start & 0xFFFFFFFFull));
+        if (used) {
+            const uint64_t pos = start + (uint64_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+            if (pos < max_entries) {
+                keys_out[pos] = slot_key(s);
+                counts_out[pos] = slot_count(s);
+            }
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uint64_t src_capacity,
+                            uint32_t *status, hipStream_t stream) {
+    uint64_t blocks = (src_capacity + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(ocm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dst, dst_capacity, src, src_capacity,
+                       status);
+    return hipGetLastError();
+}
+
+hipError_t launch_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *keys_out, uint32_t *counts_out,
+                             uint64_t max_entries, uint64_t *n_out, hipStream_t stream) {
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, stream, (unsigned long long *)n_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    uint64_t blocks = (capacity + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(ocm_export_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ocm, capacity, keys_out, counts_out,
+                       max_entries, (unsigned long long *)n_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream) {

@@ -361,6 +361,7 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
             if (m_bad) atomicAdd(&a.status[CSD_STATUS_BAD_DRAFT], (uint32_t)__builtin_popcountll(m_bad));
             if (m_rescued) atomicAdd(&a.status[CSD_STATUS_RESCUED], (uint32_t)__builtin_popcountll(m_rescued));
             if (m_counted) atomicAdd(&a.status[CSD_STATUS_COUNTED], (uint32_t)__builtin_popcountll(m_counted));
+            if (n) atomicAdd(&a.status[CSD_STATUS_ACCEPTED], (uint32_t)n);
         }
     }
 }

@@ -74,7 +74,7 @@ def compare_table(ocm: torch.Tensor, orc: O.CSDOracle, where: str = ""):
 
 
 def run_stream(workload, steps, tau=None, lam=None, capacity=None, prior=None, check_table_every=50,
-               threads=8, apply_updates=True):
+               threads=8, apply_updates=True, progress_every=0):
     """Drive `steps` decode steps through csd_verify and the oracle; compare every step."""
     cfg = workload.cfg
     tau = cfg.tau if tau is None else tau
@@ -103,6 +103,8 @@ def run_stream(workload, steps, tau=None, lam=None, capacity=None, prior=None, c
         counted += sum(len(l) for l in res.log)
         if check_table_every and (step % check_table_every == 0):
             compare_table(ocm, orc, where)
+        if progress_every and (step % progress_every == 0):
+            print("%s ok, %d rescued, %d counted, %d pairs" % (where, rescued, counted, len(orc.T)), flush=True)
     compare_table(ocm, orc, cfg.name + " final")
     st = bf.status.cpu().numpy().view(np.uint32)
     assert st[csd.CSD_STATUS_RESCUED] == rescued and st[csd.CSD_STATUS_COUNTED] == counted

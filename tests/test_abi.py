@@ -93,4 +93,10 @@ def test_argument_errors_are_synchronous_and_enqueue_nothing():
     assert lib.csd_ocm_update(P(good), 1024, P(good + 1), None, 5, None, None) == b.CSD_EALIGN
     assert lib.csd_ocm_lookup(P(good), 1024, P(good), None, 5, None) == b.CSD_EINVAL
     assert lib.csd_ocm_lookup(P(good), 3, P(good), P(good), 5, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_merge(P(good), 1024, P(good + 0x10000), 1000, None, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_merge(P(good), 1024, P(good + 64), 1024, None, None) == b.CSD_EINVAL     # overlapping tables
+    assert lib.csd_ocm_merge(P(good), 1024, None, 1024, None, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_export(P(good), 1024, None, None, 5, P(good), None) == b.CSD_EINVAL
+    assert lib.csd_ocm_export(P(good), 1024, P(good), P(good), 5, None, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_export(P(good), 1024, P(good), P(good + 2), 5, P(good), None) == b.CSD_EALIGN
     assert b.csd_strerror(b.CSD_ENOSPACE) == "workspace too small"

@@ -1,4 +1,6 @@
 """GPU parity: csd_verify / csd_ocm_* through the C ABI against the fp64 oracle (needs an MI355X)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -43,6 +45,17 @@ def test_full_size_steps_with_prior(ci, steps):
     prior = _prior_from_pairs(w, w.cfg.lam, n=min(512, w.cfg.n_pairs))
     orc, ocm, rescued, counted = run_stream(w, range(steps), prior=prior, check_table_every=1, threads=16)
     assert rescued > 0
+
+
+@pytest.mark.skipif(os.environ.get("CSD_FULL_STREAMS") != "1",
+                    reason="several minutes of oracle time per configuration: set CSD_FULL_STREAMS=1 and run with -s")
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_full_streams_every_step(ci):
+    """Configs 1-4 exactly as stated: full size, every step of the stream (2000/2000/1000/500), memory
+    evolving from empty, every step compared and the memory compared every 100 steps."""
+    w = Workload(CONFIGS[ci])
+    orc, ocm, rescued, counted = run_stream(w, range(w.cfg.steps), check_table_every=100, threads=16, progress_every=20)
+    assert rescued > 0 and counted > w.cfg.steps
 
 
 # --------------------------------------------------------------------------- row statistics: shapes, ties, ranges
@@ -273,7 +286,7 @@ def test_ocm_update_duplicates_weights_lookup():
     ocm = csd.new_ocm(1 << 16)
     orc = O.CSDOracle(capacity=1 << 16)
     keys = torch.from_numpy(((d.astype(np.int64) << 20) | t.astype(np.int64))).cuda()
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(csd.CSD_STATUS_WORDS, dtype=torch.int32, device="cuda")
     csd.csd_ocm_update(ocm, keys, torch.from_numpy(wts).cuda(), status)
     csd.csd_ocm_update(ocm, keys[:1000], None, status)
     orc.ocm_update(zip(d.tolist(), t.tolist()), wts.tolist())
@@ -309,7 +322,7 @@ def test_ocm_hot_key_contention_and_saturation():
 
 def test_ocm_full_table_drops_are_reported():
     ocm = csd.new_ocm(8)
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(csd.CSD_STATUS_WORDS, dtype=torch.int32, device="cuda")
     orc = O.CSDOracle(capacity=8)
     for j in range(12):                      # one new key per call: which insert is dropped is then well defined
         key = torch.tensor([((j + 1) << 20) | (j + 100)], dtype=torch.int64, device="cuda")
@@ -324,6 +337,124 @@ def test_ocm_full_table_drops_are_reported():
     assert csd.csd_ocm_lookup(ocm, keys).cpu().tolist() == [4, 0]
     csd.csd_ocm_reset(ocm)
     assert csd.decode_ocm(ocm) == {}
+
+
+def test_ocm_merge_export_rehash_roundtrip():
+    """Life cycle of the memory: export as a list, reload the list, grow by merging into a larger table,
+    fold two memories calibrated separately."""
+    rng = np.random.default_rng(12)
+    def random_memory(n, seed):
+        r = np.random.default_rng(seed)
+        d = r.integers(0, 3000, size=n)
+        t = (d + 1 + r.integers(0, 40, size=n)) % 3000
+        keep = d != t
+        d, t = d[keep], t[keep]
+        wts = r.integers(1, 1000, size=d.size).astype(np.int32)
+        orc = O.CSDOracle()
+        orc.ocm_update(zip(d.tolist(), t.tolist()), wts.tolist())
+        ocm = csd.new_ocm(1 << 15)
+        csd.csd_ocm_update(ocm, torch.from_numpy((d.astype(np.int64) << 20) | t.astype(np.int64)).cuda(),
+                           torch.from_numpy(wts).cuda())
+        return orc, ocm
+    orc_a, ocm_a = random_memory(9000, 1)
+    orc_b, ocm_b = random_memory(7000, 2)
+    compare_table(ocm_a, orc_a, "a")
+    # export: the same pairs and counts as the oracle's dict, any order
+    keys, counts, n = csd.csd_ocm_export(ocm_a)
+    n = int(n.item())
+    assert n == len(orc_a.T)
+    got = {(int(x) >> 20, int(x) & 0xFFFFF): int(c) for x, c in zip(keys[:n].cpu().tolist(), counts[:n].cpu().tolist())}
+    assert got == orc_a.ocm_export()
+    # count-only call, and a list shorter than the table
+    _, _, n0 = csd.csd_ocm_export(ocm_a, max_entries=0)
+    assert int(n0.item()) == n
+    k5, c5, n5 = csd.csd_ocm_export(ocm_a, max_entries=5)
+    assert int(n5.item()) == n
+    assert all(got[(int(x) >> 20, int(x) & 0xFFFFF)] == int(c) for x, c in zip(k5.cpu().tolist(), c5.cpu().tolist()))
+    # the exported list reloads into an empty table of another size
+    ocm_c = csd.new_ocm(1 << 14)
+    csd.csd_ocm_update(ocm_c, keys[:n], counts[:n])
+    compare_table(ocm_c, orc_a, "reloaded")
+    # growth: a larger empty table takes the old one
+    big = csd.new_ocm(1 << 17)
+    status = torch.zeros(csd.CSD_STATUS_WORDS, dtype=torch.int32, device="cuda")
+    csd.csd_ocm_merge(big, ocm_a, status)
+    compare_table(big, orc_a, "grown")
+    # folding a second memory in: counts of common pairs add
+    csd.csd_ocm_merge(big, ocm_b, status)
+    orc_a.ocm_merge(orc_b)
+    compare_table(big, orc_a, "folded")
+    assert len(set(orc_b.T) & set(orc_a.T)) > 0 and int(status[csd.CSD_STATUS_DROPPED]) == 0
+    # saturation carries through a merge
+    sat = csd.new_ocm(16)
+    csd.csd_ocm_update(sat, torch.tensor([(5 << 20) | 6], dtype=torch.int64, device="cuda"),
+                       torch.tensor([csd.CSD_OCM_COUNT_MAX - 3], dtype=torch.int32, device="cuda"))
+    sat2 = sat.clone()
+    csd.csd_ocm_merge(sat, sat2)
+    assert csd.decode_ocm(sat) == {(5, 6): csd.CSD_OCM_COUNT_MAX}
+
+
+def test_two_streams_share_one_memory():
+    """Concurrent verification calls on one table (each with its own buffers and stream): counts stay
+    exact.  With a threshold no count can reach, no lookup can change an outcome, so the result is the
+    oracle's whatever the interleaving."""
+    lam = 2 ** 32 - 1
+    wa, wb = Workload(CONFIGS[4], V=4000, B=48), Workload(CONFIGS[4], V=4000, B=48, seed=5)
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    steps = 25
+    ins = []
+    for step in range(steps):
+        za, da = wa.step(step)
+        zb, db = wb.step(step)
+        ins.append((za, da, zb, db, to_device_logits(za), torch.from_numpy(da).cuda(), to_device_logits(zb),
+                    torch.from_numpy(db).cuda()))
+    torch.cuda.synchronize()
+    bfa = bfb = None
+    outs = []
+    for za, da, zb, db, zta, dta, ztb, dtb in ins:                  # both streams run ahead without host syncs
+        with torch.cuda.stream(sa):
+            bfa = csd.csd_verify(zta, dta, 0.3, lam, ocm, buffers=bfa)
+            outs.append(bfa.accept_len.clone())
+        with torch.cuda.stream(sb):
+            bfb = csd.csd_verify(ztb, dtb, 0.3, lam, ocm, buffers=bfb)
+            outs.append(bfb.accept_len.clone())
+    torch.cuda.synchronize()
+    j = 0
+    for za, da, zb, db, *_ in ins:
+        for z, d in ((za, da), (zb, db)):
+            res = orc.verify_step(z, d, tau=np.float32(0.3), lam=lam)
+            np.testing.assert_array_equal(outs[j].cpu().numpy(), res.accept_len)
+            j += 1
+    compare_table(ocm, orc, "two streams")
+
+
+def test_ablation_ordering_on_one_memory():
+    """Per sequence, on the same frozen memory: strict <= full method <= min(memory only, gate only);
+    the acceptance counter of the status block equals the sum of the accept lengths."""
+    w = Workload(CONFIGS[2], V=6000, B=64)
+    cfg = w.cfg
+    prior = _prior_from_pairs(w, cfg.lam, n=600)
+    ocm = csd.new_ocm(1 << 13)
+    csd.csd_ocm_update(ocm, torch.tensor([(d << 20) | t for d, t in prior[0]], dtype=torch.int64, device="cuda"),
+                       torch.tensor(prior[1], dtype=torch.int32, device="cuda"))
+    seen_rescue = False
+    for step in range(8):
+        z, draft = w.step(step)
+        zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+        def run(tau, lam, table):
+            bf = csd.csd_verify(zt, dt, tau, lam, table, flags=0)
+            torch.cuda.synchronize()
+            assert int(bf.status[csd.CSD_STATUS_ACCEPTED]) == int(bf.accept_len.sum())
+            return bf.accept_len.cpu().numpy().copy()
+        strict = run(cfg.tau, cfg.lam, None)
+        full = run(cfg.tau, cfg.lam, ocm)
+        mem_only = run(0.0, cfg.lam, ocm)
+        gate_only = run(cfg.tau, 0, ocm)
+        assert np.all(strict <= full) and np.all(full <= np.minimum(mem_only, gate_only))
+        seen_rescue |= bool(np.any(full > strict))
+    assert seen_rescue
 
 
 def test_verify_on_a_side_stream():

@@ -337,3 +337,16 @@ def test_capacity_drop_and_saturation_and_bad_ids():
     res = o2.verify_step(z, np.array([[1, 7]], dtype=np.int32), tau=0.0, lam=0)
     assert res.accept_len[0] == 1 and res.next_token[0] == 1
     assert res.ratio[0, 1] == 0.0 and res.p_draft[0, 1] == 0.0 and not o2.T and o2.bad_draft == 1
+
+
+def test_memory_merge_and_export_are_plain_dictionary_sums():
+    """Folding one memory into another adds counts pair by pair (saturating, same drop rule as an update);
+    the export is the table itself."""
+    a, b = O.CSDOracle(capacity=4), O.CSDOracle()
+    a.ocm_update([(1, 2), (3, 4)], [5, 7])
+    b.ocm_update([(3, 4), (5, 6), (7, 8), (9, 10)], [1, O.COUNT_MAX, 2, 3])
+    a.ocm_merge(b)
+    assert a.ocm_export() == {(1, 2): 5, (3, 4): 8, (5, 6): O.COUNT_MAX, (7, 8): 2}
+    assert a.dropped == 3                      # the fifth distinct pair found the four slots taken
+    a.ocm_merge(b)
+    assert a.T[(5, 6)] == O.COUNT_MAX and a.T[(3, 4)] == 9
