@@ -108,3 +108,72 @@ def test_planted_mistakes_in_row_statistics_are_caught(tmp_path, monkeypatch):
             with pytest.raises(AssertionError):
                 pin()
         monkeypatch.undo()
+
+
+# --------------------------------------------------------------------------- the sampling-temperature oracle
+import test_oracle_sampled as sampled_pins
+from oracle import csd_oracle_sampled as OS
+
+_SRC_S = open(OS.__file__.replace(".pyc", ".py")).read()
+
+MUTANTS_SAMPLED = [
+    ("inverted_acceptance_ratio", "min(1.0, p[d] / q[d])", "min(1.0, q[d] / p[d])"),
+    ("exclusive_acceptance_test", "if r <= res.alpha[b, i]:", "if r < res.alpha[b, i]:"),
+    ("residual_sign", "w = np.maximum(0.0, p - q)", "w = np.maximum(0.0, q - p)"),
+    ("residual_not_clamped", "w = np.maximum(0.0, p - q)", "w = np.abs(p - q)"),
+    ("residual_is_target", "w = np.maximum(0.0, p - q)", "w = p"),
+    ("inverse_cdf_boundary_rule", 'side="right"', 'side="left"'),
+    ("gate_on_tempered_probabilities", "res.ratio[b, i] = np.exp(z[d] - z[t])", "res.ratio[b, i] = p[d] / p[t]"),
+    ("inverted_gate_ratio", "res.ratio[b, i] = np.exp(z[d] - z[t])", "res.ratio[b, i] = np.exp(z[t] - z[d])"),
+    ("temperature_ignored", "e = np.exp((z64 - m) / T)", "e = np.exp(z64 - m)"),
+    ("lookup_after_update", "snapshot.get((d, ts), 0) >= lam", "snapshot.get((d, ts), 0) + 1 >= lam"),
+    ("reversed_pair", "pending.append((d, ts))", "pending.append((ts, d))"),
+    ("count_only_final_rejections", "            pending.append((d, ts))\n", "            pending.append((d, ts)) if not (is_freq and is_safe) else None\n"),
+    ("bonus_from_wrong_row", "pk = softmax_T(widen(zp[b, k]), T)", "pk = softmax_T(widen(zp[b, k - 1]), T)"),
+    ("emits_draft_token_on_stop", "                res.next_token[b] = ts\n", "                res.next_token[b] = d\n"),
+    ("rescue_needs_only_gate", "if is_freq and is_safe:", "if is_safe:"),
+    ("keeps_going_after_stop", "                res.next_token[b] = ts\n                stopped = True\n                break",
+     "                res.next_token[b] = ts\n                stopped = True\n                continue"),
+]
+
+SAMPLED_PINS = [
+    sampled_pins.test_worked_example,
+    sampled_pins.test_inverse_cdf_against_a_plain_loop_and_its_edges,
+    lambda: sampled_pins.test_emitted_token_follows_the_target_distribution(5, 1.0, 0),
+    lambda: sampled_pins.test_emitted_token_follows_the_target_distribution(7, 0.6, 1),
+    sampled_pins.test_bonus_token_follows_p_of_the_last_row,
+    sampled_pins.test_small_temperature_reduces_to_the_greedy_oracle,
+    sampled_pins.test_gate_uses_raw_logits_whatever_the_temperature,
+    sampled_pins.test_counts_equal_bruteforce_recount_and_snapshot_rule,
+    sampled_pins.test_equal_models_accept_everything,
+]
+
+
+def _load_sampled_mutant(old, new):
+    assert _SRC_S.count(old) >= 1, "mutation site not found: " + old
+    mod = types.ModuleType("oracle.csd_oracle_sampled_mutant")
+    mod.__file__ = OS.__file__
+    mod.__package__ = "oracle"
+    sys.modules["oracle.csd_oracle_sampled_mutant"] = mod
+    exec(compile(_SRC_S.replace(old, new, 1), "csd_oracle_sampled_mutant", "exec"), mod.__dict__)
+    return mod
+
+
+def _sampled_failures(monkeypatch, mod):
+    monkeypatch.setattr(sampled_pins, "OS", mod)
+    failed = 0
+    for pin in SAMPLED_PINS:
+        try:
+            pin()
+        except (AssertionError, KeyError, IndexError, TypeError):
+            failed += 1
+    return failed
+
+
+def test_unmutated_sampled_copy_passes_every_pin(monkeypatch):
+    assert _sampled_failures(monkeypatch, _load_sampled_mutant("snapshot = orc.T", "snapshot = orc.T ")) == 0
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS_SAMPLED, ids=[m[0] for m in MUTANTS_SAMPLED])
+def test_planted_mistake_in_sampled_oracle_is_caught(monkeypatch, name, old, new):
+    assert _sampled_failures(monkeypatch, _load_sampled_mutant(old, new)) >= 1, name
