@@ -272,3 +272,65 @@ class Workload:
         if self.cfg.dtype == "bf16":
             return bf16_bits_to_f32(logits)
         return logits
+
+
+class SampledWorkload(Workload):
+    """Decode steps for verification at a sampling temperature: target logits and draft tokens as in
+    Workload, plus the draft model's logits and the uniform random numbers of the step.
+
+    Draft row of position i: independent N(0, sigma^2) noise, the drafted token planted 8 above the noise
+    maximum (the draft model is confident of what it drafted), and - when the drafted token is not the
+    target's top token - the target's top token planted ``U(0,3)`` below that (the draft model also gives
+    it weight, so that the residual max(0, p - q) is concentrated but not a single spike).
+    u_accept [B][k] and u_draw [B][k+1] are uniform in [0, 1) (float32).  Nothing here evaluates the
+    acceptance test or a distribution: keeping the random numbers away from decision boundaries is the
+    test harness's job, with the oracle."""
+
+    def empty_sampled_step(self):
+        cfg = self.cfg
+        dt = np.float32 if cfg.dtype == "f32" else np.uint16
+        return (np.empty((cfg.B, cfg.K1, cfg.V), dtype=dt), np.empty((cfg.B, cfg.k, cfg.V), dtype=dt),
+                np.empty((cfg.B, cfg.k), dtype=np.int32))
+
+    def _draft_row(self, step: int, b: int, i: int, d: int, target_row: np.ndarray, out_row: np.ndarray) -> None:
+        cfg = self.cfg
+        rowkey = (step << 34) | (b << 10) | i
+        key0 = self._key0 | (1 << 31)
+        rn = np.random.Generator(np.random.Philox(key=[key0, 2 * rowkey]))
+        rs = np.random.Generator(np.random.Philox(key=[key0, 2 * rowkey + 1]))
+        noise = rn.standard_normal(cfg.V, dtype=np.float32)
+        noise *= np.float32(cfg.sigma)
+        nmax = float(noise.max())
+        if cfg.dtype == "bf16":
+            out_row[:] = f32_to_bf16_bits(noise)
+        else:
+            out_row[:] = noise
+        top = self._quant_scalar(nmax + SPIKE)
+        self._store(out_row, d, top)
+        t = int(np.argmax(self.logits_as_f32(target_row)))        # the planted top of the target row
+        if t != d:
+            self._store(out_row, t, self._quant_scalar(top - float(rs.random()) * DELTA_MAX))
+
+    def sampled_step(self, step: int, threads: int = 1, out=None):
+        """(target logits [B][k+1][V], draft logits [B][k][V], draft [B][k], u_accept [B][k], u_draw [B][k+1])."""
+        cfg = self.cfg
+        zp, zq, draft = out if out is not None else self.empty_sampled_step()
+
+        def work(job):
+            b, i = job
+            d, _ = self._row(step, b, i, zp[b, i])
+            if i < cfg.k:
+                draft[b, i] = d
+                self._draft_row(step, b, i, d, zp[b, i], zq[b, i])
+
+        jobs = [(b, i) for b in range(cfg.B) for i in range(cfg.K1)]
+        if threads > 1 and len(jobs) > 1:
+            with ThreadPoolExecutor(max_workers=threads) as ex:
+                list(ex.map(work, jobs))
+        else:
+            for j in jobs:
+                work(j)
+        ru = np.random.Generator(np.random.Philox(key=[self._key0 | (1 << 31), (1 << 62) | step]))
+        u_accept = ru.random((cfg.B, cfg.k), dtype=np.float32)
+        u_draw = ru.random((cfg.B, cfg.K1), dtype=np.float32)
+        return zp, zq, draft, u_accept, u_draw

@@ -139,6 +139,48 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
                void *stream);
 
 /*
+ * csd_verify_sampled - one verification step at a sampling temperature T > 0 (Algorithm 1 as printed:
+ * acceptance test of Eq. 2, correction token from the normalised residual, memory, gate of Eq. 3).  The
+ * uniform random numbers the algorithm draws are inputs, so that a run can be reproduced and checked.
+ *
+ * Per draft position i, with p_i = softmax(target row i / T) and q_i = softmax(draft row i / T):
+ *   the draft token is kept when u_accept[b][i] <= min(1, p_i(draft) / q_i(draft));
+ *   otherwise t* is drawn from norm(max(0, p_i - q_i)): the smallest token id whose running residual
+ *   mass (ascending id) exceeds u_draw[b][i] * (total mass); then T[(draft, t*)] >= lambda and
+ *   exp(z(draft) - z(t*)) >= tau on the raw target logits decide the rescue exactly as in csd_verify,
+ *   the pair is counted, and the loop stops with t* as the emitted token unless rescued.
+ *   When all k tokens are kept the emitted token is drawn from p_{k+1} with u_draw[b][k].
+ *
+ * Inputs that differ from csd_verify
+ *   target_logits [B][k+1][V], draft_logits [B][k][V]   same dtype, each with its own row stride;
+ *                 values as for csd_verify, and |z| / T within the same 2^29 bound
+ *   temperature   T, 0 < T <= 1e6
+ *   u_accept      [B][k] float in [0,1]: the r of the acceptance test
+ *   u_draw        [B][k+1] float in [0,1): residual draws of positions 0..k-1, bonus draw at index k
+ * Outputs
+ *   accept_len [B], next_token [B], pos_flags [B][k] (CSD_POS_MATCH = kept by the acceptance test),
+ *   rej_log, status: as for csd_verify
+ *   tstar       [B][k]  residual draw of every position whose acceptance test failed (also those the loop
+ *                       did not reach), -1 elsewhere (nullable)
+ *   bonus_token [B]     the draw from p_{k+1}, computed for every sequence (nullable)
+ *   alpha, p_draft, q_draft [B][k]  min(1,p/q), p_i(draft), q_i(draft) at temperature T (nullable)
+ *   ratio       [B][k]  exp(z(draft) - z(t*)) where the acceptance test failed, 0 elsewhere (nullable)
+ * A draw whose u * mass falls within rounding of a boundary of the running sum may land on either
+ * neighbour; a residual without any mass reports the target row's argmax.  An id outside [0,V) ends
+ * the loop uncounted with the row's argmax as the emitted token.
+ * Five launches: the streaming pass over all 2k+1 rows per sequence, the acceptance test, a second
+ * streaming pass over the rows that need a draw (target and draft row side by side), the inversion of
+ * the running sum, and the loop with the memory updates.
+ */
+size_t csd_verify_sampled_workspace_bytes(int B, int k, int V, int dtype);
+int csd_verify_sampled(const void *target_logits, const void *draft_logits, int dtype, int64_t target_row_stride,
+                       int64_t draft_row_stride, const int32_t *draft, int B, int k, int V, float temperature,
+                       const float *u_accept, const float *u_draw, float tau, uint32_t lambda, uint64_t *ocm,
+                       uint64_t capacity, uint32_t flags, int32_t *accept_len, int32_t *next_token, int32_t *tstar,
+                       int32_t *bonus_token, float *alpha, float *p_draft, float *q_draft, float *ratio, uint8_t *pos_flags,
+                       uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * csd_ocm_update - add counts to the table (UpdateMemory of Algorithm 1 as a separate call; also the
  * bulk load of a calibrated prior, Online Correction Memory phase 1).
  *   keys     [n] CSD_OCM_KEY(draft, target); bits above the key field are ignored; entries equal to

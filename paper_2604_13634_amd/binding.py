@@ -56,6 +56,11 @@ def load_library() -> ctypes.CDLL:
     lib.csd_verify.restype = i32
     lib.csd_verify.argtypes = [vp, i32, i64, vp, i32, i32, i32, f32, u32, vp, u64, u32,
                                vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csd_verify_sampled_workspace_bytes.restype = sz
+    lib.csd_verify_sampled_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.csd_verify_sampled.restype = i32
+    lib.csd_verify_sampled.argtypes = [vp, vp, i32, i64, i64, vp, i32, i32, i32, f32, vp, vp, f32, u32, vp, u64, u32,
+                                       vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.csd_ocm_update.restype = i32
     lib.csd_ocm_update.argtypes = [vp, u64, vp, vp, u64, vp, vp]
     lib.csd_ocm_reset.restype = i32
@@ -177,6 +182,87 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
         _ptr(bf.workspace), bf.workspace.numel(), _stream(stream))
     if rc != CSD_OK:
         raise CsdError(rc, "csd_verify")
+    return bf
+
+
+def csd_verify_sampled_workspace_bytes(B: int, k: int, V: int, dtype: int) -> int:
+    return int(load_library().csd_verify_sampled_workspace_bytes(B, k, V, dtype))
+
+
+@dataclass
+class SampledBuffers:
+    """Outputs and scratch of csd_verify_sampled for one shape, allocated once and reused across calls."""
+    B: int
+    k: int
+    V: int
+    dtype: int
+    accept_len: torch.Tensor
+    next_token: torch.Tensor
+    tstar: torch.Tensor
+    bonus_token: torch.Tensor
+    alpha: torch.Tensor
+    p_draft: torch.Tensor
+    q_draft: torch.Tensor
+    ratio: torch.Tensor
+    pos_flags: torch.Tensor
+    rej_log: torch.Tensor
+    status: torch.Tensor
+    workspace: torch.Tensor
+
+    @staticmethod
+    def allocate(B: int, k: int, V: int, dtype: int, device="cuda") -> "SampledBuffers":
+        nbytes = csd_verify_sampled_workspace_bytes(B, k, V, dtype)
+        if nbytes == 0:
+            raise CsdError(CSD_EINVAL, "csd_verify_sampled_workspace_bytes")
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        return SampledBuffers(
+            B, k, V, dtype,
+            accept_len=e((B,), torch.int32), next_token=e((B,), torch.int32), tstar=e((B, k), torch.int32),
+            bonus_token=e((B,), torch.int32), alpha=e((B, k), torch.float32), p_draft=e((B, k), torch.float32),
+            q_draft=e((B, k), torch.float32), ratio=e((B, k), torch.float32), pos_flags=e((B, k), torch.uint8),
+            rej_log=e((B, k), torch.int64), status=torch.zeros((CSD_STATUS_WORDS,), dtype=torch.int32, device=device),
+            workspace=e((nbytes,), torch.uint8))
+
+
+def _rows_stride(t: torch.Tensor, what: str) -> int:
+    if t.dim() != 3 or t.stride(2) != 1 or (t.shape[0] > 1 and t.shape[1] > 0 and t.stride(0) != t.shape[1] * t.stride(1)):
+        raise ValueError(what + " must be [B][rows][V] with equally spaced rows and unit element stride")
+    return t.stride(1) if (t.shape[0] * t.shape[1]) > 1 else max(t.shape[2], t.stride(1))
+
+
+def csd_verify_sampled(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft: torch.Tensor, temperature: float,
+                       u_accept: torch.Tensor, u_draw: torch.Tensor, tau: float, lam: int,
+                       ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+                       buffers: Optional[SampledBuffers] = None, stream=None, diagnostics: bool = True) -> SampledBuffers:
+    """Enqueue one verification step at a sampling temperature.  target_logits [B][k+1][V], draft_logits [B][k][V]
+    (same dtype), draft [B][k] int32, u_accept [B][k] and u_draw [B][k+1] float32."""
+    B, K1, V = target_logits.shape
+    k = K1 - 1
+    if tuple(draft_logits.shape) != (B, k, V) or draft_logits.dtype != target_logits.dtype:
+        raise ValueError("draft_logits must be [B][k][V] of the target's dtype")
+    if draft.dtype != torch.int32 or tuple(draft.shape) != (B, k) or not draft.is_contiguous():
+        raise ValueError("draft must be a contiguous int32 [B][k] tensor")
+    for t, shape, name in ((u_accept, (B, k), "u_accept"), (u_draw, (B, K1), "u_draw")):
+        if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(name + " must be a contiguous float32 tensor of shape %r" % (shape,))
+    dt = _dtype_code(target_logits)
+    if buffers is None:
+        buffers = SampledBuffers.allocate(B, k, V, dt, target_logits.device)
+    elif (buffers.B, buffers.k, buffers.V, buffers.dtype) != (B, k, V, dt):
+        raise ValueError("buffers were allocated for another shape")
+    if ocm is not None and (ocm.dtype != torch.int64 or not ocm.is_contiguous()):
+        raise ValueError("ocm must be a contiguous int64 tensor")
+    bf = buffers
+    opt = (lambda t: _ptr(t)) if diagnostics else (lambda t: None)
+    rc = load_library().csd_verify_sampled(
+        _ptr(target_logits), _ptr(draft_logits) if k else None, dt, _rows_stride(target_logits, "target_logits"),
+        _rows_stride(draft_logits, "draft_logits") if k else V, _ptr(draft), B, k, V, float(temperature),
+        _ptr(u_accept), _ptr(u_draw), float(tau), int(lam) & 0xFFFFFFFF, _ptr(ocm), 0 if ocm is None else ocm.numel(),
+        int(flags), _ptr(bf.accept_len), _ptr(bf.next_token), opt(bf.tstar), opt(bf.bonus_token), opt(bf.alpha),
+        opt(bf.p_draft), opt(bf.q_draft), opt(bf.ratio), opt(bf.pos_flags), opt(bf.rej_log), _ptr(bf.status),
+        _ptr(bf.workspace), bf.workspace.numel(), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_verify_sampled")
     return bf
 
 

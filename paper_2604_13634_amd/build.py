@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcsd.so")
-SOURCES = ["csd_verify.hip", "csd_ocm.hip", "csd_api.hip"]
+SOURCES = ["csd_verify.hip", "csd_sampled.hip", "csd_ocm.hip", "csd_api.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

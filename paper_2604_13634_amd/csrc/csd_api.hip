@@ -96,10 +96,120 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     // very large batches hand them to the bulk update kernel instead (one more launch, many workgroups).
     const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
     a.apply_updates = update_in_finish ? 1 : 0;
-    if (launch_row_partials(logits, dtype, row_stride, V, plan, partials, a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
+    const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, plan.rows, nullptr, 0, CSD_LOG2E_F32};
+    if (launch_row_partials(src, dtype, V, plan, partials, a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
     if (launch_finish(a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_in_finish) {
         if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
+    }
+    return CSD_OK;
+}
+
+static SampledWorkspace sampled_layout(const StreamPlan &plan, int B, int k, int nseg) {
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    SampledWorkspace w;
+    const size_t K1 = (size_t)k + 1;
+    w.ticket_off = 0;
+    w.partials_off = 256;
+    w.rows_off = up(w.partials_off + (size_t)plan.rows * plan.partials_per_row * sizeof(RowPartial));
+    w.segsum_off = up(w.rows_off + (size_t)B * K1 * sizeof(DrawRow));
+    w.zpd_off = up(w.segsum_off + (size_t)B * K1 * (size_t)nseg * sizeof(float));
+    w.state_off = up(w.zpd_off + (size_t)B * k * sizeof(float));
+    w.tstar_off = up(w.state_off + (size_t)B * k);
+    w.bonus_off = up(w.tstar_off + (size_t)B * k * sizeof(int32_t));
+    w.log_off = up(w.bonus_off + (size_t)B * sizeof(int32_t));
+    w.total = up(w.log_off + (size_t)B * k * sizeof(uint64_t));
+    return w;
+}
+
+size_t csd_verify_sampled_workspace_bytes(int B, int k, int V, int dtype) {
+    if (!shape_ok(B, k, V, dtype)) return 0;
+    if ((int64_t)B * (2 * k + 1) > (int64_t)1 << 24) return 0;
+    const StreamPlan p = make_stream_plan(B * (2 * k + 1), V, dtype);
+    return sampled_layout(p, B, k, sampled_segments(V, dtype)).total;
+}
+
+int csd_verify_sampled(const void *target_logits, const void *draft_logits, int dtype, int64_t target_row_stride,
+                       int64_t draft_row_stride, const int32_t *draft, int B, int k, int V, float temperature,
+                       const float *u_accept, const float *u_draw, float tau, uint32_t lambda, uint64_t *ocm,
+                       uint64_t capacity, uint32_t flags, int32_t *accept_len, int32_t *next_token, int32_t *tstar,
+                       int32_t *bonus_token, float *alpha, float *p_draft, float *q_draft, float *ratio, uint8_t *pos_flags,
+                       uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!shape_ok(B, k, V, dtype) || (int64_t)B * (2 * k + 1) > (int64_t)1 << 24) return CSD_EINVAL;
+    if (is_nan_bits(tau) || is_nan_bits(temperature) || !(temperature > 0.f) || temperature > 1e6f) return CSD_EINVAL;
+    const float scale = (float)(1.4426950408889634 / (double)temperature);
+    if (!(scale > 1e-6f) || !(scale < 1e6f)) return CSD_EINVAL;
+    if (flags & ~CSD_APPLY_UPDATES) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    if (!target_logits || !accept_len || !next_token || !workspace || !u_draw) return CSD_EINVAL;
+    if (k > 0 && (!draft || !draft_logits || !u_accept)) return CSD_EINVAL;
+    if (target_row_stride < V || (k > 0 && draft_row_stride < V)) return CSD_EINVAL;
+    if (ocm && !is_pow2(capacity)) return CSD_EINVAL;
+    const size_t esz = (dtype == CSD_DTYPE_F32) ? 4 : 2;
+    if (!aligned(target_logits, 16) || ((size_t)target_row_stride * esz) % 16 != 0) return CSD_EALIGN;
+    if (k > 0 && (!aligned(draft_logits, 16) || ((size_t)draft_row_stride * esz) % 16 != 0)) return CSD_EALIGN;
+    if (!aligned(workspace, 16) || !aligned(accept_len, 4) || !aligned(next_token, 4) || !aligned(tstar, 4) ||
+        !aligned(bonus_token, 4) || !aligned(draft, 4) || !aligned(u_accept, 4) || !aligned(u_draw, 4) || !aligned(alpha, 4) ||
+        !aligned(p_draft, 4) || !aligned(q_draft, 4) || !aligned(ratio, 4) || !aligned(rej_log, 8) || !aligned(ocm, 8) ||
+        !aligned(status, 4))
+        return CSD_EALIGN;
+
+    const int rows_p = B * (k + 1), rows_q = B * k;
+    const StreamPlan plan = make_stream_plan(rows_p + rows_q, V, dtype);
+    const int nseg = sampled_segments(V, dtype);
+    const SampledWorkspace ws = sampled_layout(plan, B, k, nseg);
+    if (workspace_bytes < ws.total) return CSD_ENOSPACE;
+    char *wsp = (char *)workspace;
+    hipStream_t st = (hipStream_t)stream;
+    const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
+
+    SampledArgs a;
+    a.target = target_logits;
+    a.draft_logits = draft_logits;
+    a.dtype = dtype;
+    a.target_stride = target_row_stride;
+    a.draft_stride = draft_row_stride;
+    a.draft = draft;
+    a.B = B;
+    a.k = k;
+    a.V = V;
+    a.scale = scale;
+    a.u_accept = u_accept;
+    a.u_draw = u_draw;
+    a.tau = tau;
+    a.lambda = lambda;
+    a.ocm = ocm;
+    a.capacity = capacity;
+    a.partials = (const RowPartial *)(wsp + ws.partials_off);
+    a.partials_per_row = plan.partials_per_row;
+    a.nseg = nseg;
+    a.rows = (DrawRow *)(wsp + ws.rows_off);
+    a.segsum = (float *)(wsp + ws.segsum_off);
+    a.pos_zpd = (float *)(wsp + ws.zpd_off);
+    a.pos_state = (uint8_t *)(wsp + ws.state_off);
+    a.tstar = tstar ? tstar : (int32_t *)(wsp + ws.tstar_off);
+    a.bonus = bonus_token ? bonus_token : (int32_t *)(wsp + ws.bonus_off);
+    a.accept_len = accept_len;
+    a.next_token = next_token;
+    a.alpha = alpha;
+    a.p_draft = p_draft;
+    a.q_draft = q_draft;
+    a.ratio = ratio;
+    a.pos_flags = pos_flags;
+    a.rej_log = rej_log ? rej_log : (apply ? (uint64_t *)(wsp + ws.log_off) : nullptr);
+    a.status = status;
+    a.batch_ticket = (uint32_t *)(wsp + ws.ticket_off);
+    const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
+    a.apply_updates = update_in_finish ? 1 : 0;
+
+    const StreamSource src = {(const char *)target_logits, target_row_stride * (int64_t)esz, rows_p,
+                              (const char *)draft_logits, draft_row_stride * (int64_t)esz, scale};
+    if (launch_row_partials(src, dtype, V, plan, (RowPartial *)(wsp + ws.partials_off), a.batch_ticket, st) != hipSuccess)
+        return CSD_EHIP;
+    if (launch_sampled_tail(a, st) != hipSuccess) return CSD_EHIP;
+    if (apply && !update_in_finish) {
+        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess)
+            return CSD_EHIP;
     }
     return CSD_OK;
 }
@@ -160,7 +270,8 @@ int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows
     if (!aligned(logits, 16) || ((size_t)row_stride * esz) % 16 != 0 || !aligned(partials, 16)) return CSD_EALIGN;
     const StreamPlan plan = make_stream_plan(rows, V, dtype);
     if (partials_bytes < (size_t)rows * plan.partials_per_row * sizeof(RowPartial)) return CSD_ENOSPACE;
-    return launch_row_partials(logits, dtype, row_stride, V, plan, partials, nullptr, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+    const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, rows, nullptr, 0, CSD_LOG2E_F32};
+    return launch_row_partials(src, dtype, V, plan, partials, nullptr, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
 const char *csd_strerror(int code) {

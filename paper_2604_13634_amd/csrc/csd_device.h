@@ -178,6 +178,130 @@ __device__ __forceinline__ void block_apply_batch(uint64_t *ocm, uint64_t capaci
     __syncthreads();                                // the next batch reuses the LDS arrays
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- 16-byte chunk of logits -> fp32 values (bf16 widening is exact)
+template <int DT> struct Chunk;
+template <> struct Chunk<CSD_DTYPE_F32> {
+    static constexpr int E = 4;
+    static constexpr uint32_t kNegInfWord = 0xFF800000u;
+    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
+        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
+        x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+    }
+    // the last, partial chunk of a row: n < E logits starting at element v0, the rest -inf
+    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
+        const uint32_t *p = (const uint32_t *)row + v0;
+        u32x4 q = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+        if (n > 0) q.x = p[0];
+        if (n > 1) q.y = p[1];
+        if (n > 2) q.z = p[2];
+        return q;
+    }
+};
+template <> struct Chunk<CSD_DTYPE_BF16> {
+    static constexpr int E = 8;
+    static constexpr uint32_t kNegInfWord = 0xFF80FF80u;
+    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
+        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xFFFF0000u);
+        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xFFFF0000u);
+        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xFFFF0000u);
+        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xFFFF0000u);
+    }
+    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
+        const uint16_t *p = (const uint16_t *)row + v0;
+        uint32_t w[4] = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+#pragma unroll
+        for (int j = 0; j < 7; ++j) {
+            if (j < n) {
+                const uint32_t h = p[j];
+                w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | (h << 16)) : ((w[j >> 1] & 0xFFFF0000u) | h);
+            }
+        }
+        u32x4 q = {w[0], w[1], w[2], w[3]};
+        return q;
+    }
+};
+
+template <int E>
+__device__ __forceinline__ float chunk_max(const float (&x)[E]) {
+    float m = x[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) m = __builtin_fmaxf(m, x[j]);
+    return m;
+}
+
+// ---- data handed between workgroups: agent-scope relaxed atomics, 64 bits at a time
+__device__ __forceinline__ void xwg_store64(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t xwg_load64(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One atomic ticket per workgroup: true in every thread of the workgroup that drew the last of `total`
+// tickets.  Every wave first waits until its own vector-memory operations are acknowledged
+// (s_waitcnt vmcnt(0): on gfx9 the counter covers stores, and a write-through store is acknowledged once
+// it is visible at agent scope) - a workgroup barrier alone does not wait for them.  The second barrier
+// hands the verdict round; the reads of the log depend on it, so they cannot be issued early.
+__device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int *verdict) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0); expcnt and lgkmcnt left alone
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *verdict = (old == total - 1);
+    }
+    __syncthreads();
+    return *verdict != 0;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Combine the P partials of one row, shared by a group of G lanes (G a power of two; lane gs of the group
+// takes partials gs, gs+G, ...; a butterfly over the group finishes).  One pass: running maximum gm, its
+// lowest token id t, and S kept relative to gm.  `scale` is the exponent scale the partials were made
+// with (log2e / temperature), as a double holding the float value.  Every lane of the group gets the result.
+__device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
+                                                     int &t, double &S) {
+    gm = -INFINITY;
+    t = 0x7fffffff;
+    S = 0.0;
+    for (int j = gs; j < P; j += G) {
+        const RowPartial q = pp[j];
+        if (q.m > gm || (q.m == gm && q.idx < t)) t = q.idx;
+        if (q.s != 0.f) {                                       // then q.m is finite
+            const float mn = fmaxf(gm, q.m);
+            const double ref = (double)mn * scale;              // exact: two 24-bit significands
+            const double keep = (S != 0.0) ? S * exp2((double)gm * scale - ref) : 0.0;
+            S = keep + (double)q.s * exp2((double)q.cref - ref);
+        }
+        gm = fmaxf(gm, q.m);
+    }
+    for (int x = 1; x < G; x <<= 1) {
+        const float om = xchg_f(gm, x);
+        const int ot = xchg_i(t, x);
+        const double oS = xchg_d(S, x);
+        if (om > gm || (om == gm && ot < t)) t = ot;
+        const float mn = fmaxf(gm, om);
+        const double ref = (double)mn * scale;
+        const double mine = (S != 0.0) ? S * exp2((double)gm * scale - ref) : 0.0;
+        const double theirs = (oS != 0.0) ? oS * exp2((double)om * scale - ref) : 0.0;
+        S = mine + theirs;
+        gm = mn;
+    }
+}
+
+// The tail of a step: the workgroup that draws the last of gridDim.x tickets applies the step's log of n
+// entries (every lookup of the step has then been made).  Called by every thread of every workgroup.
+constexpr int kFinishWaves = kApplyThreads / kWaveSize;
+__device__ __forceinline__ void apply_step_log(uint64_t *ocm, uint64_t capacity, uint32_t *status, const uint64_t *rej_log,
+                                               uint64_t n, uint32_t *ticket, ApplyLds &lds, int *verdict) {
+    if (!take_last_ticket(ticket, gridDim.x, verdict)) return;
+    auto fetch = [&](uint64_t e, uint64_t &key, uint32_t &w) {
+        key = xwg_load64(&rej_log[e]) & CSD_OCM_KEY_MASK;
+        w = 1u;
+    };
+    for (uint64_t base = 0; base < n; base += kApplyBatch) block_apply_batch(ocm, capacity, status, lds, fetch, base, n);
+}
+
 __device__ __forceinline__ float load_logit(const void *logits, int dtype, int64_t elem) {
     if (dtype == CSD_DTYPE_F32) return ((const float *)logits)[elem];
     return __uint_as_float((uint32_t)((const uint16_t *)logits)[elem] << 16);

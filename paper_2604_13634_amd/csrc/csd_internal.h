@@ -69,9 +69,74 @@ struct EpilogueArgs {
     int apply_updates;
 };
 
+// Where the rows of a streaming launch live: rows [0, rows0) in tensor 0, the others in tensor 1
+// (pitches in bytes), and the exponent scale log2(e) / temperature the sums are made with.
+struct StreamSource {
+    const char *base0;
+    int64_t pitch0;
+    int rows0;
+    const char *base1;
+    int64_t pitch1;
+    float scale;
+};
+
+// ---- verification at a sampling temperature (csd_sampled.hip)
+// What the residual kernels need for one draw row (a rejected draft position, or the bonus row).
+struct DrawRow {
+    int32_t need;      // 0: nothing is drawn for this row
+    int32_t fallback;  // the target row's argmax: reported when the residual has no mass, or the draft id was invalid
+    float cp, fp;      // p_v = 2^(z_v * scale - cp) * fp
+    float cq, fq;      // q_v likewise; unused for the bonus row, which draws from p itself
+    float u;           // the uniform of this draw
+    float pad;
+};
+static_assert(sizeof(DrawRow) == 32, "draw rows are 32-byte records");
+
+struct SampledArgs {
+    const void *target;        // [B][k+1][V]
+    const void *draft_logits;  // [B][k][V]
+    int dtype;
+    int64_t target_stride, draft_stride;   // elements
+    const int32_t *draft;
+    int B, k, V;
+    float scale;               // log2(e) / temperature, as the streaming pass used it
+    const float *u_accept;     // [B][k]
+    const float *u_draw;       // [B][k+1]
+    float tau;
+    uint32_t lambda;
+    uint64_t *ocm;
+    uint64_t capacity;
+    const RowPartial *partials;   // target rows first, then draft rows
+    int partials_per_row;
+    int nseg;                  // segments per row
+    DrawRow *rows;             // [B][k+1]
+    float *segsum;             // [B][k+1][nseg]
+    float *pos_zpd;            // [B][k] target logit of the draft token
+    uint8_t *pos_state;        // [B][k] bit0 acceptance test failed, bit1 draft id valid
+    int32_t *tstar;            // [B][k] user buffer or workspace
+    int32_t *bonus;            // [B]    user buffer or workspace
+    int32_t *accept_len;
+    int32_t *next_token;
+    float *alpha;
+    float *p_draft;
+    float *q_draft;
+    float *ratio;
+    uint8_t *pos_flags;
+    uint64_t *rej_log;
+    uint32_t *status;
+    uint32_t *batch_ticket;
+    int apply_updates;
+};
+
+struct SampledWorkspace {
+    size_t ticket_off, partials_off, rows_off, segsum_off, zpd_off, state_off, tstar_off, bonus_off, log_off, total;
+};
+int sampled_segments(int V, int dtype);
+hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);
+
 // kernel launchers (enqueue only; return hipGetLastError())
-hipError_t launch_row_partials(const void *logits, int dtype, int64_t row_stride, int V, const StreamPlan &plan,
-                               RowPartial *partials, uint32_t *batch_ticket, hipStream_t stream);
+hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
+                               uint32_t *batch_ticket, hipStream_t stream);
 hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream);

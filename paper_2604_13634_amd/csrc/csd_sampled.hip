@@ -1,0 +1,391 @@
+// Verification at a sampling temperature T > 0: Algorithm 1's loop as printed, with the uniform random
+// numbers it draws handed in by the caller.
+//
+//   per draft position i:  p_i = softmax(target logits / T),  q_i = softmax(draft logits / T)
+//     accept x~ when r <= min(1, p_i(x~)/q_i(x~))                                              (Eq. 2)
+//     else draw t* from norm(max(0, p_i - q_i)) by inverting its running sum at u (ascending token id),
+//          look (x~, t*) up in the memory, gate on exp(z(x~) - z(t*)) of the raw target logits (Eq. 3),
+//          count the pair, then keep x~ (rescued) or stop and emit t*
+//   all kept: emit a draw from p_{k+1}.
+//
+// Five launches on the caller's stream:
+//   1. row_partials_kernel (csd_verify.hip) over the B(k+1) target rows and the Bk draft rows in one grid,
+//      with the exponent scale log2(e)/T: maxima and normalisers at temperature T.        [HBM-bound]
+//   2. sampled_decide_kernel, one wave per sequence: combine the partials, p(x~), q(x~), alpha, the
+//      acceptance test; leaves for every "draw row" (a rejected position, or the bonus row) the constants
+//      that turn a logit into a probability.
+//   3. residual_segments_kernel over the draw rows only: streams the target row and the draft row side
+//      by side and leaves the residual mass of every segment of 256 chunks.               [HBM-bound]
+//   4. residual_locate_kernel, one wave per draw row: scans the segment masses in double, finds the
+//      segment that holds u*R, re-reads that one segment and walks to the token.
+//   5. sampled_finish_kernel, one wave per sequence: lookup, gate, accepted-prefix scan, emitted token,
+//      log; the last workgroup applies the step's updates (same tail as the greedy path).
+// Positions whose acceptance test fails are all drawn (the draws do not depend on each other), although
+// the loop may stop before it reaches some of them; so is the bonus token of every sequence.
+#include "csd_device.h"
+
+namespace csd {
+namespace {
+
+constexpr int kSegLoads = 4;                          // 16-byte loads per lane and segment
+constexpr int kSegChunks = kWaveSize * kSegLoads;     // chunks per segment (one wave sweeps a segment)
+constexpr int kSegsPerWave = 4;                       // segments one wave of the segment kernel takes
+constexpr int kSegBlockWaves = 4;
+constexpr int kNone = 0x7fffffff;
+
+// probability of one logit from the row constants: 2^(z*scale - c) * f.  Separate roundings (no
+// contraction) so that the segment pass and the locate pass see the same numbers.
+__device__ __forceinline__ float prob_of(float z, float scale, float c, float f) {
+    return __fmul_rn(__builtin_amdgcn_exp2f(__builtin_fmaf(z, scale, -c)), f);
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 load_chunk_guarded(const char *row, int ch, int nfull, int tail) {
+    using C = Chunk<DT>;
+    u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
+    if (ch < nfull) q = ((const u32x4 *)row)[ch];
+    else if (ch == nfull && tail > 0) q = C::load_ragged(row, nfull * C::E, tail);
+    return q;
+}
+
+// residual weights of one chunk: w = max(0, p - q), or p itself for the bonus row (use_q false)
+template <int DT>
+__device__ __forceinline__ void chunk_weights(const char *prow, const char *qrow, bool use_q, int ch, int nfull, int tail,
+                                              float scale, const DrawRow &r, float (&w)[Chunk<DT>::E]) {
+    using C = Chunk<DT>;
+    float x[C::E];
+    C::unpack(load_chunk_guarded<DT>(prow, ch, nfull, tail), x);
+#pragma unroll
+    for (int j = 0; j < C::E; ++j) w[j] = prob_of(x[j], scale, r.cp, r.fp);
+    if (use_q) {
+        float y[C::E];
+        C::unpack(load_chunk_guarded<DT>(qrow, ch, nfull, tail), y);
+#pragma unroll
+        for (int j = 0; j < C::E; ++j) w[j] = __builtin_fmaxf(__fsub_rn(w[j], prob_of(y[j], scale, r.cq, r.fq)), 0.f);
+    }
+}
+
+// exclusive prefix sum over the 64 lanes, in double; `total` = the wave's sum, the same value in every lane
+__device__ __forceinline__ double wave_exclusive_scan_d(double v, int lane, double &total) {
+    double incl = v;
+#pragma unroll
+    for (int off = 1; off < kWaveSize; off <<= 1) {
+        const double o = from_lane_d(incl, lane >= off ? lane - off : lane);
+        if (lane >= off) incl += o;
+    }
+    total = from_lane_d(incl, kWaveSize - 1);
+    return incl - v;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Launch 2: acceptance test.  One wave per sequence; lane i < k owns draft position i, lane i <= k draw row i.
+__global__ __launch_bounds__(kApplyThreads) void sampled_decide_kernel(SampledArgs a) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    if (b >= a.B) return;
+    const int k = a.k, K1 = a.k + 1, P = a.partials_per_row;
+    const bool is_pos = lane < k;
+    const double scale = (double)a.scale;
+
+    int d = -1;
+    bool valid = false;
+    float zpd = 0.f, zqd = 0.f;
+    if (is_pos) {
+        d = a.draft[(int64_t)b * k + lane];
+        valid = (d >= 0) && (d < a.V);
+        if (valid) {
+            zpd = load_logit(a.target, a.dtype, ((int64_t)b * K1 + lane) * a.target_stride + d);
+            zqd = load_logit(a.draft_logits, a.dtype, ((int64_t)b * k + lane) * a.draft_stride + d);
+        }
+    }
+    int G = 1;
+    while (2 * G * K1 <= kWaveSize) G *= 2;
+    const int grow = lane / G, gs = lane & (G - 1);
+    const int src = (lane < K1 ? lane : 0) * G;          // lane i takes the statistics of row i
+
+    float gm;
+    int gt;
+    double gS;
+    combine_row_partials(a.partials + ((int64_t)b * K1 + (grow < K1 ? grow : 0)) * P, P, G, gs, scale, gm, gt, gS);
+    const float mp = from_lane_f(gm, src);
+    const int tp = from_lane_i(gt, src);
+    const double Sp = from_lane_d(gS, src);
+    float mq = 0.f;
+    double Sq = 1.0;
+    if (k > 0) {
+        const int64_t qrow0 = (int64_t)a.B * K1 + (int64_t)b * k;   // draft rows follow the target rows
+        combine_row_partials(a.partials + (qrow0 + (grow < k ? grow : 0)) * P, P, G, gs, scale, gm, gt, gS);
+        mq = from_lane_f(gm, src);
+        Sq = from_lane_d(gS, src);
+    }
+
+    bool rejected = false;
+    if (is_pos) {
+        double pd = 0.0, qd = 0.0, alpha = 0.0;
+        rejected = true;                                   // an id outside the vocabulary never passes
+        if (valid) {
+            pd = exp2(((double)zpd - (double)mp) * scale) / Sp;
+            qd = exp2(((double)zqd - (double)mq) * scale) / Sq;
+            alpha = (qd <= 0.0) ? 1.0 : fmin(1.0, pd / qd);
+            rejected = (double)a.u_accept[(int64_t)b * k + lane] > alpha;
+        }
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.alpha) a.alpha[o] = (float)alpha;
+        if (a.p_draft) a.p_draft[o] = (float)pd;
+        if (a.q_draft) a.q_draft[o] = (float)qd;
+        a.pos_zpd[o] = zpd;
+        a.pos_state[o] = (uint8_t)((rejected ? 1 : 0) | (valid ? 2 : 0));
+    }
+    if (lane < K1) {
+        DrawRow r;
+        r.need = (lane == k) ? 1 : ((rejected && valid) ? 1 : 0);
+        r.fallback = tp;
+        r.cp = mp * a.scale;                               // float reference exponent near m*scale ...
+        r.fp = (float)(exp2((double)r.cp - (double)mp * scale) / Sp);   // ... and what it leaves out, with 1/S
+        r.cq = 0.f;
+        r.fq = 0.f;
+        if (lane < k) {
+            r.cq = mq * a.scale;
+            r.fq = (float)(exp2((double)r.cq - (double)mq * scale) / Sq);
+        }
+        r.u = a.u_draw[(int64_t)b * K1 + lane];
+        r.pad = 0.f;
+        a.rows[(int64_t)b * K1 + lane] = r;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Launch 3: residual mass per segment, draw rows only.  grid.x = draw row, grid.y = groups of segments.
+template <int DT>
+__global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
+    using C = Chunk<DT>;
+    const int j = blockIdx.x;
+    const DrawRow r = a.rows[j];
+    if (!r.need) return;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int K1 = a.k + 1;
+    const int b = j / K1, i = j - b * K1;
+    const bool use_q = i < a.k;
+    const int esz = (DT == CSD_DTYPE_F32) ? 4 : 2;
+    const char *prow = (const char *)a.target + (int64_t)j * a.target_stride * esz;
+    const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
+    const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
+    const int seg0 = (blockIdx.y * kSegBlockWaves + wave) * kSegsPerWave;
+    for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; ++s) {
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < kSegLoads; ++u) {
+            float w[C::E];
+            chunk_weights<DT>(prow, qrow, use_q, s * kSegChunks + u * kWaveSize + lane, nfull, tail, a.scale, r, w);
+#pragma unroll
+            for (int e = 0; e < C::E; ++e) sum += w[e];
+        }
+        sum = wave_allreduce_f(sum, AddF());
+        if (lane == 0) a.segsum[(int64_t)j * a.nseg + s] = sum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Launch 4: invert the running sum.  One wave per draw row.
+template <int DT>
+__global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledArgs a) {
+    using C = Chunk<DT>;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int K1 = a.k + 1;
+    const int64_t j = (int64_t)blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    if (j >= (int64_t)a.B * K1) return;
+    const int b = (int)(j / K1), i = (int)(j - (int64_t)b * K1);
+    int32_t *out = (i < a.k) ? &a.tstar[(int64_t)b * a.k + i] : &a.bonus[b];
+    const DrawRow r = a.rows[j];
+    if (!r.need) {
+        if (lane == 0) *out = -1;
+        return;
+    }
+    // ---- which segment: lane l owns segments [l*per, (l+1)*per)
+    const float *seg = a.segsum + j * a.nseg;
+    const int per = (a.nseg + kWaveSize - 1) / kWaveSize;
+    const int s0 = lane * per;
+    double local = 0.0;
+    for (int s = s0; s < s0 + per && s < a.nseg; ++s) local += (double)seg[s];
+    double R;
+    const double before = wave_exclusive_scan_d(local, lane, R);
+    int result = -1;
+    if (R > 0.0) {
+        const double target = (double)r.u * R;
+        int found = kNone, lastpos = -1;
+        double base = 0.0, acc = before;
+        for (int s = s0; s < s0 + per && s < a.nseg; ++s) {
+            const double v = (double)seg[s];
+            if (v > 0.0) lastpos = s;
+            if (found == kNone && acc + v > target) {
+                found = s;
+                base = acc;
+            }
+            acc += v;
+        }
+        int sstar = wave_allreduce_i(found, MinI());
+        if (sstar == kNone) {                              // rounding at the very end of the row: last segment with mass
+            sstar = -wave_allreduce_i(-lastpos, MinI());
+            base = 0.0;
+            found = kNone - 1;                             // nobody owns `base`: walk the segment from its start with rem = +inf
+        }
+        const int owner = sstar / per;
+        double rem = (found == kNone - 1) ? INFINITY : target - from_lane_d(base, owner);
+        // ---- inside the segment, in token order: load u, then lane, then element
+        const int esz = (DT == CSD_DTYPE_F32) ? 4 : 2;
+        const bool use_q = i < a.k;
+        const char *prow = (const char *)a.target + j * a.target_stride * esz;
+        const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
+        const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
+        int last_tok = -1;
+        for (int u = 0; u < kSegLoads && result < 0; ++u) {
+            const int ch = sstar * kSegChunks + u * kWaveSize + lane;
+            float w[C::E];
+            chunk_weights<DT>(prow, qrow, use_q, ch, nfull, tail, a.scale, r, w);
+            double lsum = 0.0;
+            int my_last = -1;
+#pragma unroll
+            for (int e = 0; e < C::E; ++e) {
+                lsum += (double)w[e];
+                if (w[e] > 0.f) my_last = ch * C::E + e;
+            }
+            last_tok = my_last > last_tok ? my_last : last_tok;
+            double tot;
+            const double excl = wave_exclusive_scan_d(lsum, lane, tot);
+            const uint64_t hit = __builtin_amdgcn_ballot_w64(excl + lsum > rem);
+            if (hit) {
+                const int L = (int)__builtin_ctzll(hit);
+                int tok = my_last;
+                if (lane == L) {
+                    double c = excl;
+                    bool done = false;
+#pragma unroll
+                    for (int e = 0; e < C::E; ++e) {
+                        c += (double)w[e];
+                        if (!done && c > rem) {
+                            tok = ch * C::E + e;
+                            done = true;
+                        }
+                    }
+                }
+                result = from_lane_i(tok, L);
+            } else {
+                rem -= tot;
+            }
+        }
+        if (result < 0) result = -wave_allreduce_i(-last_tok, MinI());   // rounding: the segment's last token with mass
+    }
+    if (result < 0) result = r.fallback;                   // no residual mass at all: the target's own choice
+    if (lane == 0) *out = result;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Launch 5: the loop itself.  One wave per sequence.
+__device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, int lane) {
+    const int k = a.k, K1 = a.k + 1;
+    const bool is_pos = lane < k;
+    int d = -1, t = -1;
+    bool valid = false, rejected = false;
+    float zpd = 0.f, zpt = 0.f;
+    if (is_pos) {
+        const int64_t o = (int64_t)b * k + lane;
+        d = a.draft[o];
+        const uint8_t st = a.pos_state[o];
+        rejected = st & 1;
+        valid = st & 2;
+        zpd = a.pos_zpd[o];
+        t = a.tstar[o];
+        if (rejected && valid) zpt = load_logit(a.target, a.dtype, ((int64_t)b * K1 + lane) * a.target_stride + t);
+    }
+    const bool diverges = is_pos && rejected && valid;
+    // Eq. 3 on the raw target logits
+    const double ratio = diverges ? exp2(((double)zpd - (double)zpt) * 1.4426950408889634) : 0.0;
+    if (is_pos && a.ratio) a.ratio[(int64_t)b * k + lane] = (float)ratio;
+    const uint64_t key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? t : 0));
+    bool is_freq = false;
+    if (diverges && a.ocm != nullptr) is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, key) >= a.lambda);
+    const bool is_safe = diverges && (ratio >= (double)a.tau);
+    const bool ok = is_pos && (!rejected || (is_freq && is_safe));
+
+    const uint64_t fail = __builtin_amdgcn_ballot_w64(is_pos && !ok) | (1ull << k);
+    const int n = (int)__builtin_ctzll(fail);
+    const bool processed = is_pos && (lane <= n);
+    const bool counted = processed && diverges;
+    // emitted token: the stopping position's t* (the target argmax when its draft id was invalid), else the bonus draw
+    int mine = (diverges ? t : a.rows[(int64_t)b * K1 + (lane < K1 ? lane : 0)].fallback);
+    if (lane == k) mine = a.bonus[b];
+    const int next = from_lane_i(mine, n);
+
+    if (is_pos) {
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.pos_flags) {
+            uint8_t f = 0;
+            if (processed) {
+                if (!rejected) f = CSD_POS_MATCH | CSD_POS_ACCEPTED;
+                else if (diverges)
+                    f = CSD_POS_COUNTED | (is_freq ? CSD_POS_FREQ : 0) | (is_safe ? CSD_POS_SAFE : 0) |
+                        (ok ? CSD_POS_ACCEPTED : 0);
+            }
+            a.pos_flags[o] = f;
+        }
+        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? key : CSD_OCM_EMPTY);
+    }
+    const uint64_t m_counted = __builtin_amdgcn_ballot_w64(counted);
+    const uint64_t m_rescued = __builtin_amdgcn_ballot_w64(counted && ok);
+    const uint64_t m_bad = __builtin_amdgcn_ballot_w64(processed && !valid);
+    if (lane == 0) {
+        a.accept_len[b] = n;
+        a.next_token[b] = next;
+        if (a.status) {
+            if (m_bad) atomicAdd(&a.status[CSD_STATUS_BAD_DRAFT], (uint32_t)__builtin_popcountll(m_bad));
+            if (m_rescued) atomicAdd(&a.status[CSD_STATUS_RESCUED], (uint32_t)__builtin_popcountll(m_rescued));
+            if (m_counted) atomicAdd(&a.status[CSD_STATUS_COUNTED], (uint32_t)__builtin_popcountll(m_counted));
+            if (n) atomicAdd(&a.status[CSD_STATUS_ACCEPTED], (uint32_t)n);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kApplyThreads) void sampled_finish_kernel(SampledArgs a) {
+    __shared__ ApplyLds lds;
+    __shared__ int verdict;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    if (b < a.B) sampled_sequence(a, b, lane);
+    if (!a.apply_updates) return;
+    apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
+}
+
+}  // namespace
+
+int sampled_segments(int V, int dtype) {
+    const int e = (dtype == CSD_DTYPE_F32) ? 4 : 8;
+    const int nchunks = (V + e - 1) / e;
+    return (nchunks + kSegChunks - 1) / kSegChunks;
+}
+
+hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream) {
+    if (a.B == 0) return hipSuccess;
+    const int K1 = a.k + 1;
+    const dim3 seq_grid((unsigned)((a.B + kFinishWaves - 1) / kFinishWaves)), seq_block(kApplyThreads);
+    hipLaunchKernelGGL(sampled_decide_kernel, seq_grid, seq_block, 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int per_block = kSegBlockWaves * kSegsPerWave;
+    const dim3 seg_grid((unsigned)(a.B * K1), (unsigned)((a.nseg + per_block - 1) / per_block));
+    const dim3 row_grid((unsigned)(((int64_t)a.B * K1 + kFinishWaves - 1) / kFinishWaves));
+    if (a.dtype == CSD_DTYPE_F32) {
+        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(residual_locate_kernel<CSD_DTYPE_F32>, row_grid, seq_block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_BF16>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(residual_locate_kernel<CSD_DTYPE_BF16>, row_grid, seq_block, 0, stream, a);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(sampled_finish_kernel, seq_grid, seq_block, 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace csd

@@ -14,9 +14,9 @@
 //   increased and best_it = its iteration, i.e. the first chunk of this lane that holds rm (a lane
 //   visits chunks in ascending address order, so "first" is "lowest token id"); s[E] = sums of
 //   2^(z*log2e - c), one per element slot of a chunk, against a WAVE-UNIFORM reference exponent c.
-//   c is not the running maximum: it is only kept within kRescaleGap of it, which is all floating point
+//   c is not the running maximum: it is only kept within kRescaleGapLog2 of it (in exponent units), which is all floating point
 //   needs (no overflow, full relative precision).  A rescale (wave reduction + multiply) happens only
-//   when some lane's maximum climbs more than kRescaleGap above the reference - at the first tile, then
+//   when some lane's maximum climbs more than that above the reference - at the first tile, then
 //   almost never - so the steady-state loop is unpack, max3, fma, v_exp_f32, add and one compare per
 //   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
 //   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
@@ -38,93 +38,18 @@
 namespace csd {
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr float kLog2e = CSD_LOG2E_F32;
 constexpr double kLog2eD = (double)CSD_LOG2E_F32;
-constexpr float kRescaleGap = 20.0f;   // logit units; 20*log2e < 32 keeps the exponent's ulp at 2^-19 or finer
+constexpr float kRescaleGapLog2 = 28.8f;   // reference stays within this of the maximum, in exponent (log2) units:
+                                           // 20 logits at temperature 1; below 32 keeps the exponent's ulp at 2^-19 or finer
 constexpr int kNoIter = 0x7fffffff;
 constexpr int kRemIter = 1 << 30;      // best_it values at or above this index the remainder loop
-
-// ---- 16-byte chunk of logits -> fp32 values (bf16 widening is exact)
-template <int DT> struct Chunk;
-template <> struct Chunk<CSD_DTYPE_F32> {
-    static constexpr int E = 4;
-    static constexpr uint32_t kNegInfWord = 0xFF800000u;
-    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
-        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
-        x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
-    }
-    // the last, partial chunk of a row: n < E logits starting at element v0, the rest -inf
-    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
-        const uint32_t *p = (const uint32_t *)row + v0;
-        u32x4 q = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
-        if (n > 0) q.x = p[0];
-        if (n > 1) q.y = p[1];
-        if (n > 2) q.z = p[2];
-        return q;
-    }
-};
-template <> struct Chunk<CSD_DTYPE_BF16> {
-    static constexpr int E = 8;
-    static constexpr uint32_t kNegInfWord = 0xFF80FF80u;
-    __device__ static __forceinline__ void unpack(const u32x4 &q, float (&x)[E]) {
-        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xFFFF0000u);
-        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xFFFF0000u);
-        x[4] = __uint_as_float(q.z << 16); x[5] = __uint_as_float(q.z & 0xFFFF0000u);
-        x[6] = __uint_as_float(q.w << 16); x[7] = __uint_as_float(q.w & 0xFFFF0000u);
-    }
-    __device__ static __forceinline__ u32x4 load_ragged(const char *row, int v0, int n) {
-        const uint16_t *p = (const uint16_t *)row + v0;
-        uint32_t w[4] = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
-#pragma unroll
-        for (int j = 0; j < 7; ++j) {
-            if (j < n) {
-                const uint32_t h = p[j];
-                w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | (h << 16)) : ((w[j >> 1] & 0xFFFF0000u) | h);
-            }
-        }
-        u32x4 q = {w[0], w[1], w[2], w[3]};
-        return q;
-    }
-};
-
-template <int E>
-__device__ __forceinline__ float chunk_max(const float (&x)[E]) {
-    float m = x[0];
-#pragma unroll
-    for (int j = 1; j < E; ++j) m = __builtin_fmaxf(m, x[j]);
-    return m;
-}
-
-// ---- data handed between workgroups: agent-scope relaxed atomics, 64 bits at a time
-__device__ __forceinline__ void xwg_store64(uint64_t *p, uint64_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t xwg_load64(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// One atomic ticket per workgroup: true in every thread of the workgroup that drew the last of `total`
-// tickets.  Every wave first waits until its own vector-memory operations are acknowledged
-// (s_waitcnt vmcnt(0): on gfx9 the counter covers stores, and a write-through store is acknowledged once
-// it is visible at agent scope) - a workgroup barrier alone does not wait for them.  The second barrier
-// hands the verdict round; the reads of the log depend on it, so they cannot be issued early.
-__device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int *verdict) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0); expcnt and lgkmcnt left alone
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *verdict = (old == total - 1);
-    }
-    __syncthreads();
-    return *verdict != 0;
-}
 
 // ---------------------------------------------------------------------------------------------------
 // Phase 1: this wave's share of one row -> one RowPartial (returned in lane-uniform registers).
 template <int DT>
 __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ rowp, int V, int nsplit, int split,
-                                                       int wave, int lane) {
+                                                       int wave, int lane, float scale) {
     using C = Chunk<DT>;
     constexpr int E = C::E;
     constexpr int W = kStreamWaves;
@@ -147,16 +72,17 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
     for (int j = 0; j < E; ++j) s[j] = 0.f;
     float c = 0.f;             // wave-uniform reference exponent (log2 units)
     float mth = -INFINITY;     // rescale when a lane maximum exceeds this
+    const float gap = kRescaleGapLog2 / scale;   // the same distance in logit units
     const int lane_chunk0 = wave * kWaveSize + lane;
 
     auto rescale = [&]() {
         const float wm = wave_allreduce_f(rm, MaxF());
-        const float cn = wm * kLog2e;
+        const float cn = wm * scale;
         const float sc = __builtin_amdgcn_exp2f(c - cn);
 #pragma unroll
         for (int j = 0; j < E; ++j) s[j] = (s[j] == 0.f) ? 0.f : s[j] * sc;
         c = cn;
-        mth = wm + kRescaleGap;
+        mth = wm + gap;
     };
 
     // ---- whole tiles: U independent non-temporal 16-byte loads per lane.
@@ -187,7 +113,7 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][j], kLog2e, nc));
+            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][j], scale, nc));
         }
     }
 
@@ -215,7 +141,7 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
             if (__builtin_amdgcn_ballot_w64(rm > mth) != 0) rescale();
             const float nc = -c;
 #pragma unroll
-            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], kLog2e, nc));
+            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], scale, nc));
         }
     }
 
@@ -272,33 +198,10 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     const int grow = lane / G, gs = lane & (G - 1);
     const bool active = grow < K1;
     const RowPartial *pp = a.partials + ((int64_t)b * K1 + (active ? grow : 0)) * P;
-    // one pass: running maximum gm, its lowest token id t, and S kept relative to gm
-    float gm = -INFINITY;
-    int t = 0x7fffffff;
-    double S = 0.0;
-    for (int j = gs; j < P; j += G) {
-        const RowPartial q = pp[j];
-        if (q.m > gm || (q.m == gm && q.idx < t)) t = q.idx;
-        if (q.s != 0.f) {                                       // then q.m is finite
-            const float mn = fmaxf(gm, q.m);
-            const double ref = (double)mn * kLog2eD;            // exact: two 24-bit significands
-            const double keep = (S != 0.0) ? S * exp2((double)gm * kLog2eD - ref) : 0.0;
-            S = keep + (double)q.s * exp2((double)q.cref - ref);
-        }
-        gm = fmaxf(gm, q.m);
-    }
-    for (int x = 1; x < G; x <<= 1) {
-        const float om = xchg_f(gm, x);
-        const int ot = xchg_i(t, x);
-        const double oS = xchg_d(S, x);
-        if (om > gm || (om == gm && ot < t)) t = ot;
-        const float mn = fmaxf(gm, om);
-        const double ref = (double)mn * kLog2eD;
-        const double mine = (S != 0.0) ? S * exp2((double)gm * kLog2eD - ref) : 0.0;
-        const double theirs = (oS != 0.0) ? oS * exp2((double)om * kLog2eD - ref) : 0.0;
-        S = mine + theirs;
-        gm = mn;
-    }
+    float gm;
+    int t;
+    double S;
+    combine_row_partials(pp, P, G, gs, kLog2eD, gm, t, S);
     if (active && gs == 0) {
         const int64_t row = (int64_t)b * K1 + grow;
         a.argmax[row] = t;
@@ -367,8 +270,7 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
 }
 
 template <int DT>
-__global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kernel(const char *__restrict__ logits,
-                                                                                  int64_t row_pitch_bytes, int V, int nsplit,
+__global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kernel(StreamSource src, int V, int nsplit,
                                                                                   RowPartial *__restrict__ partials,
                                                                                   uint32_t *batch_ticket) {
     const int row = blockIdx.x / nsplit;
@@ -379,11 +281,11 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kerne
     if (batch_ticket != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
         __hip_atomic_store(batch_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    const RowPartial out = stream_row_share<DT>(logits + (int64_t)row * row_pitch_bytes, V, nsplit, split, wave, lane);
+    const char *rowp = (row < src.rows0) ? src.base0 + (int64_t)row * src.pitch0
+                                         : src.base1 + (int64_t)(row - src.rows0) * src.pitch1;
+    const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
     if (lane == 0) partials[((int64_t)row * nsplit + split) * kStreamWaves + wave] = out;   // one 16-byte store
 }
-
-constexpr int kFinishWaves = kApplyThreads / kWaveSize;
 
 __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
     __shared__ ApplyLds lds;
@@ -392,15 +294,7 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
     const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
     if (b < a.B) sequence_epilogue(a, b, lane);      // wave-uniform: a wave takes a sequence or none
     if (!a.apply_updates) return;
-    if (!take_last_ticket(a.batch_ticket, gridDim.x, &verdict)) return;
-    // Phase 3: every lookup of the step has been made; this workgroup applies the step's log.
-    const uint64_t n = (uint64_t)a.B * (uint64_t)a.k;
-    auto fetch = [&](uint64_t e, uint64_t &key, uint32_t &w) {
-        key = xwg_load64(&a.rej_log[e]) & CSD_OCM_KEY_MASK;
-        w = 1u;
-    };
-    for (uint64_t base = 0; base < n; base += kApplyBatch)
-        block_apply_batch(a.ocm, a.capacity, a.status, lds, fetch, base, n);
+    apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
 }
 
 }  // namespace
@@ -433,16 +327,16 @@ WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
     return w;
 }
 
-hipError_t launch_row_partials(const void *logits, int dtype, int64_t row_stride, int V, const StreamPlan &plan,
-                               RowPartial *partials, uint32_t *batch_ticket, hipStream_t stream) {
+hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
+                               uint32_t *batch_ticket, hipStream_t stream) {
     if (plan.rows == 0) return hipSuccess;
     const dim3 grid((unsigned)(plan.rows * plan.nsplit)), block(kStreamWaves * kWaveSize);
     if (dtype == CSD_DTYPE_F32)
-        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, (const char *)logits, row_stride * 4, V,
-                           plan.nsplit, partials, batch_ticket);
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, src, V, plan.nsplit, partials,
+                           batch_ticket);
     else
-        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, (const char *)logits, row_stride * 2, V,
-                           plan.nsplit, partials, batch_ticket);
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, src, V, plan.nsplit, partials,
+                           batch_ticket);
     return hipGetLastError();
 }
 

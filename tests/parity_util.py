@@ -110,3 +110,95 @@ def run_stream(workload, steps, tau=None, lam=None, capacity=None, prior=None, c
     assert st[csd.CSD_STATUS_RESCUED] == rescued and st[csd.CSD_STATUS_COUNTED] == counted
     assert st[csd.CSD_STATUS_DROPPED] == orc.dropped and st[csd.CSD_STATUS_BAD_DRAFT] == orc.bad_draft
     return orc, ocm, rescued, counted
+
+
+# --------------------------------------------------------------------------- verification at a sampling temperature
+from oracle import csd_oracle_sampled as OS   # noqa: E402
+
+TOL_ACCEPT = 1e-4      # |r - alpha| of every acceptance test
+TOL_DRAW = 1e-5        # probability mass between u * R and the nearer end of the drawn token's interval
+
+
+def settle_uniforms(zp, zq, draft, T, u_accept, u_draw, seed, tries=12):
+    """Move the step's random numbers away from decision boundaries, so that a float32 evaluation and the
+    float64 oracle must agree: every |r - alpha| >= TOL_ACCEPT, every draw at least TOL_DRAW of probability
+    mass inside its token's interval.  Offending numbers are re-drawn; a rejected position whose residual is
+    too finely divided for any draw to have that margin (mass spread over thousands of tail tokens) is
+    turned into an accepted one (r = 0).  Returns float32 copies."""
+    rng = np.random.default_rng(seed)
+    ua, ud = u_accept.astype(np.float32).copy(), u_draw.astype(np.float32).copy()
+    B, k = draft.shape
+    V = zp.shape[-1]
+    valid = (draft >= 0) & (draft < V)
+    for attempt in range(tries + 1):
+        r = OS.verify_step_sampled(O.CSDOracle(), zp, zq, draft, T, ua, ud, tau=0.0, lam=0, apply_updates=False)
+        bad_acc = valid & (r.accept_margin < TOL_ACCEPT) & (ua != 0)
+        bad_draw = np.zeros((B, k + 1), bool)
+        bad_draw[:, :k] = valid & r.rejected & (r.draw_margin[:, :k] < TOL_DRAW)
+        bad_draw[:, k] = r.draw_margin[:, k] < TOL_DRAW
+        if not bad_acc.any() and not bad_draw.any():
+            return ua, ud
+        if attempt >= tries - 2:
+            ua[bad_draw[:, :k]] = 0.0                       # give up on these residuals: accept the position
+            ua[bad_acc] = 0.0
+        else:
+            ua[bad_acc] = rng.random(int(bad_acc.sum()), dtype=np.float32)
+        ud[bad_draw] = rng.random(int(bad_draw.sum()), dtype=np.float32)
+    raise AssertionError("could not settle the random numbers of a step")
+
+
+def compare_sampled_step(res, bf, where: str = ""):
+    g = lambda t: t.cpu().numpy()
+    np.testing.assert_array_equal(g(bf.accept_len), res.accept_len, err_msg=where + " accept_len")
+    np.testing.assert_array_equal(g(bf.tstar), res.tstar, err_msg=where + " tstar")
+    np.testing.assert_array_equal(g(bf.bonus_token), res.bonus_token, err_msg=where + " bonus_token")
+    np.testing.assert_array_equal(g(bf.next_token), res.next_token, err_msg=where + " next_token")
+    np.testing.assert_array_equal(g(bf.pos_flags), res.flags, err_msg=where + " pos_flags")
+    assert_close(g(bf.alpha), res.alpha, where + " alpha")
+    assert_close(g(bf.p_draft), res.p_draft, where + " p_draft")
+    assert_close(g(bf.q_draft), res.q_draft, where + " q_draft")
+    assert_close(g(bf.ratio), np.minimum(res.ratio, 3.0e38), where + " ratio")
+    k = res.flags.shape[1]
+    log = g(bf.rej_log).view(np.uint64)
+    for b, pending in enumerate(res.log):
+        got = [int(x) for x in log[b] if int(x) & csd.CSD_OCM_KEY_MASK != csd.CSD_OCM_EMPTY]
+        assert got == [(d << 20) | t for d, t in pending], "%s rej_log of sequence %d" % (where, b)
+
+
+def run_sampled_stream(workload, steps, T, tau=None, lam=None, capacity=None, prior=None, check_table_every=10,
+                       threads=8, progress_every=0):
+    """Drive decode steps through csd_verify_sampled and the oracle; compare every step and the memory."""
+    cfg = workload.cfg
+    tau = cfg.tau if tau is None else tau
+    lam = cfg.lam if lam is None else lam
+    capacity = cfg.capacity if capacity is None else capacity
+    orc = O.CSDOracle(capacity=capacity)
+    ocm = csd.new_ocm(capacity)
+    if prior is not None:
+        pairs, weights = prior
+        orc.ocm_update(pairs, weights)
+        keys = torch.tensor([(d << 20) | t for d, t in pairs], dtype=torch.int64, device="cuda")
+        csd.csd_ocm_update(ocm, keys, torch.tensor(weights, dtype=torch.int32, device="cuda"))
+    bf = None
+    rescued = counted = rejected = 0
+    for step in steps:
+        zp, zq, draft, ua, ud = workload.sampled_step(step, threads=threads)
+        ua, ud = settle_uniforms(zp, zq, draft, T, ua, ud, seed=step)
+        bf = csd.csd_verify_sampled(to_device_logits(zp), to_device_logits(zq), torch.from_numpy(draft).cuda(), T,
+                                    torch.from_numpy(ua).cuda(), torch.from_numpy(ud).cuda(), tau, lam, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = OS.verify_step_sampled(orc, zp, zq, draft, T, ua, ud, tau=np.float32(tau), lam=lam)
+        where = "%s T=%g step %d" % (cfg.name, T, step)
+        compare_sampled_step(res, bf, where)
+        rescued += res.rescued
+        counted += sum(len(l) for l in res.log)
+        rejected += int(res.rejected.sum())
+        if check_table_every and (step % check_table_every == 0):
+            compare_table(ocm, orc, where)
+        if progress_every and (step % progress_every == 0):
+            print("%s ok, %d rejected, %d rescued, %d counted, %d pairs" % (where, rejected, rescued, counted, len(orc.T)),
+                  flush=True)
+    compare_table(ocm, orc, cfg.name + " final")
+    st = bf.status.cpu().numpy().view(np.uint32)
+    assert st[csd.CSD_STATUS_RESCUED] == rescued and st[csd.CSD_STATUS_COUNTED] == counted
+    return orc, ocm, rescued, counted, rejected
