@@ -93,6 +93,72 @@ def ingest_pmc(fetch_path: str, write_path: str, workload: str) -> int:
     return 0
 
 
+def bench_sampled(args, cfg) -> int:
+    """Whole-step timing of csd_verify_sampled on the sampled variant of a workload (target and draft logits,
+    uniforms as generated: nothing is compared here, so they are not moved away from decision boundaries)."""
+    import numpy as np
+    import torch
+
+    from gen.workload import SampledWorkload
+    from paper_2604_13634_amd import binding as csd
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity_util import to_device_logits
+
+    w = SampledWorkload(cfg)
+    step_bytes = (cfg.rows + cfg.B * cfg.k) * cfg.V * cfg.itemsize
+    n_ring = max(4, int(math.ceil(args.ring_bytes / step_bytes)))
+    ring = []
+    for s in range(n_ring):
+        zp, zq, d, ua, ud = w.sampled_step(s, threads=args.gen_threads)
+        ring.append((to_device_logits(zp), to_device_logits(zq), torch.from_numpy(d).cuda(), torch.from_numpy(ua).cuda(),
+                     torch.from_numpy(ud).cuda()))
+    torch.cuda.synchronize()
+    dt = csd.CSD_DTYPE_F32 if cfg.dtype == "f32" else csd.CSD_DTYPE_BF16
+    bf = csd.SampledBuffers.allocate(cfg.B, cfg.k, cfg.V, dt)
+    ocm = csd.new_ocm(cfg.capacity)
+
+    def step(i):
+        zp, zq, d, ua, ud = ring[i % n_ring]
+        csd.csd_verify_sampled(zp, zq, d, args.temperature, ua, ud, cfg.tau, cfg.lam, ocm, buffers=bf)
+
+    for i in range(args.warmup):
+        step(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    drawn = 0
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # rows the second pass streamed in the last step: two per rejected position, one per bonus draw
+    rejected = int((bf.tstar >= 0).sum().item())
+    pass2_bytes = (2 * rejected + cfg.B) * cfg.V * cfg.itemsize
+    ms = elapsed / args.steps * 1e3
+    alg = step_bytes + pass2_bytes
+    status = bf.status.cpu().numpy().view(np.uint32).tolist()
+    out = {
+        "metric": "verified draft positions/sec + achieved HBM GB/s (% of peak) of csd_verify_sampled",
+        "value": cfg.rows * args.steps / elapsed, "unit": "positions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name + "+draft_logits", "path": "sampled", "temperature": args.temperature, "B": cfg.B,
+                   "k": cfg.k, "V": cfg.V, "logits_storage": cfg.dtype, "positions_per_step": cfg.rows,
+                   "rows_streamed_first_pass": cfg.rows + cfg.B * cfg.k, "rejected_positions_last_step": rejected,
+                   "first_pass_bytes": step_bytes, "second_pass_bytes_last_step": pass2_bytes,
+                   "ms_per_step_by_stream_events": e0.elapsed_time(e1) / args.steps, "ring_steps": n_ring,
+                   "status_counters": status},
+        "roofline": {"bound": "hbm", "kernel": "whole step (five launches)", "achieved": alg / (ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_step": alg},
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +168,9 @@ def main() -> int:
     ap.add_argument("--ring-bytes", type=float, default=float(1 << 30), help="minimum bytes of distinct logits in the ring")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--path", choices=("greedy", "sampled"), default="greedy",
+                    help="greedy: csd_verify (the headline); sampled: csd_verify_sampled at --temperature")
+    ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--pmc-run", action="store_true", help="short run for rocprofv3 --pmc (see module docstring)")
     ap.add_argument("--ingest-pmc", nargs=2, metavar=("FETCH", "WRITE"))
     args = ap.parse_args()
@@ -123,6 +192,8 @@ def main() -> int:
     from parity_util import to_device_logits
 
     torch.cuda.set_device(0)
+    if args.path == "sampled":
+        return bench_sampled(args, cfg)
     w = Workload(cfg)
     rows = cfg.rows
     n_ring = max(4, int(math.ceil(args.ring_bytes / cfg.bytes_per_step)))

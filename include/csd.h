@@ -50,6 +50,7 @@ extern "C" {
 /* limits */
 #define CSD_MAX_K 63           /* draft tokens per sequence                       */
 #define CSD_MAX_V (1u << 20)   /* vocabulary size (token ids fit 20 bits)         */
+#define CSD_MAX_SHARDS 8       /* vocabulary shards csd_verify_shards merges       */
 
 /*
  * Online Correction Memory: an open-addressed table of `capacity` (a power of two) 64-bit slots,
@@ -252,6 +253,34 @@ int csd_row_partials_per_row(int rows, int V, int dtype);
  */
 int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows, int V, csd_row_partial *partials,
                      size_t partials_bytes, void *stream);
+
+/*
+ * Vocabulary shards.  When the target's logits exist only as shards of the vocabulary - a tensor-parallel
+ * LM head (the large targets span several devices), or a head evaluated chunk by chunk - each shard runs
+ * csd_row_partials on its [B*(k+1)][V_s] slice and csd_shard_draft_logits to pick out the logits of the
+ * draft tokens it owns; the partials (16 bytes each) and the [B][k] draft logits are all that has to be
+ * brought together, and csd_verify_shards does the rest of the step from them: the same combine, lookup,
+ * gate, scan and updates as csd_verify, with token ids of shard s offset by shard_base[s].
+ *
+ * csd_shard_draft_logits: draft_logit[b][i] = logits[b][i][draft[b][i] - base] where base <= draft[b][i] <
+ *   base + V_shard; other entries are left untouched (so shards on one device can share the buffer, and
+ *   buffers of several devices merge by taking, per entry, the one value that was written).
+ * csd_verify_shards:
+ *   n_shards (1..CSD_MAX_SHARDS); shard_partials, shard_per_row, shard_base: HOST arrays of n_shards entries
+ *     (device pointer to the shard's partials [B*(k+1)][shard_per_row[s]], its partials per row as
+ *     csd_row_partials_per_row reported, the token id of its first logit)
+ *   draft_logit [B][k] device; V = the whole vocabulary; everything else as csd_verify.
+ *   workspace >= csd_verify_shards_workspace_bytes(B, k).
+ */
+size_t csd_verify_shards_workspace_bytes(int B, int k);
+int csd_verify_shards(int n_shards, const csd_row_partial *const *shard_partials, const int *shard_per_row,
+                      const int *shard_base, const float *draft_logit, const int32_t *draft, int B, int k, int V, float tau,
+                      uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+                      int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+                      uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+                      void *stream);
+int csd_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
+                           const int32_t *draft, float *draft_logit, void *stream);
 
 /* Static string for a return code (host pointer, never NULL). */
 const char *csd_strerror(int code);

@@ -22,6 +22,7 @@ CSD_DTYPE_F32, CSD_DTYPE_BF16 = 0, 1
 CSD_APPLY_UPDATES = 1
 CSD_MAX_K = 63
 CSD_MAX_V = 1 << 20
+CSD_MAX_SHARDS = 8
 CSD_OCM_KEY_BITS = 40
 CSD_OCM_KEY_MASK = (1 << 40) - 1
 CSD_OCM_EMPTY = (1 << 40) - 1
@@ -61,6 +62,13 @@ def load_library() -> ctypes.CDLL:
     lib.csd_verify_sampled.restype = i32
     lib.csd_verify_sampled.argtypes = [vp, vp, i32, i64, i64, vp, i32, i32, i32, f32, vp, vp, f32, u32, vp, u64, u32,
                                        vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csd_verify_shards_workspace_bytes.restype = sz
+    lib.csd_verify_shards_workspace_bytes.argtypes = [i32, i32]
+    lib.csd_verify_shards.restype = i32
+    lib.csd_verify_shards.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, f32, u32, vp, u64, u32,
+                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csd_shard_draft_logits.restype = i32
+    lib.csd_shard_draft_logits.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp, vp, vp]
     lib.csd_ocm_update.restype = i32
     lib.csd_ocm_update.argtypes = [vp, u64, vp, vp, u64, vp, vp]
     lib.csd_ocm_reset.restype = i32
@@ -185,6 +193,53 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
     return bf
 
 
+def _rows_stride(t: torch.Tensor, what: str) -> int:
+    if t.dim() != 3 or t.stride(2) != 1 or (t.shape[0] > 1 and t.shape[1] > 0 and t.stride(0) != t.shape[1] * t.stride(1)):
+        raise ValueError(what + " must be [B][rows][V] with equally spaced rows and unit element stride")
+    return t.stride(1) if (t.shape[0] * t.shape[1]) > 1 else max(t.shape[2], t.stride(1))
+
+
+def csd_verify_shards_workspace_bytes(B: int, k: int) -> int:
+    return int(load_library().csd_verify_shards_workspace_bytes(B, k))
+
+
+def csd_shard_draft_logits(logits_shard: torch.Tensor, base: int, draft: torch.Tensor, draft_logit: torch.Tensor,
+                           stream=None) -> None:
+    """draft_logit[b][i] = logits_shard[b][i][draft[b][i] - base] for the draft tokens this shard owns."""
+    B, K1, Vs = logits_shard.shape
+    rc = load_library().csd_shard_draft_logits(_ptr(logits_shard), _dtype_code(logits_shard),
+                                               _rows_stride(logits_shard, "logits_shard"), B, K1 - 1, Vs, int(base),
+                                               _ptr(draft), _ptr(draft_logit), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_shard_draft_logits")
+
+
+def csd_verify_shards(shard_partials, shard_base, draft_logit: torch.Tensor, draft: torch.Tensor, V: int, tau: float,
+                      lam: int, ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+                      buffers: Optional[VerifyBuffers] = None, stream=None) -> VerifyBuffers:
+    """Enqueue one verification step from the row partials of vocabulary shards (tensors as returned by
+    csd_row_partials, [rows][per_row][4] int32), their first token ids, and the [B][k] draft logits."""
+    B, k = draft.shape
+    n = len(shard_partials)
+    if buffers is None:
+        buffers = VerifyBuffers.allocate(B, k, V, CSD_DTYPE_F32, draft.device)
+    bf = buffers
+    need = csd_verify_shards_workspace_bytes(B, k)
+    if bf.workspace.numel() < need:
+        bf.workspace = torch.empty((need,), dtype=torch.uint8, device=draft.device)
+    ptrs = (ctypes.c_void_p * n)(*[t.data_ptr() for t in shard_partials])
+    per_row = (ctypes.c_int * n)(*[int(t.shape[1]) for t in shard_partials])
+    bases = (ctypes.c_int * n)(*[int(x) for x in shard_base])
+    rc = load_library().csd_verify_shards(
+        n, ptrs, per_row, bases, _ptr(draft_logit), _ptr(draft), B, k, V, float(tau), int(lam) & 0xFFFFFFFF, _ptr(ocm),
+        0 if ocm is None else ocm.numel(), int(flags), _ptr(bf.accept_len), _ptr(bf.next_token), _ptr(bf.argmax),
+        _ptr(bf.row_max), _ptr(bf.row_sumexp), _ptr(bf.ratio), _ptr(bf.p_draft), _ptr(bf.pos_flags), _ptr(bf.rej_log),
+        _ptr(bf.status), _ptr(bf.workspace), bf.workspace.numel(), _stream(stream))
+    if rc != CSD_OK:
+        raise CsdError(rc, "csd_verify_shards")
+    return bf
+
+
 def csd_verify_sampled_workspace_bytes(B: int, k: int, V: int, dtype: int) -> int:
     return int(load_library().csd_verify_sampled_workspace_bytes(B, k, V, dtype))
 
@@ -222,12 +277,6 @@ class SampledBuffers:
             q_draft=e((B, k), torch.float32), ratio=e((B, k), torch.float32), pos_flags=e((B, k), torch.uint8),
             rej_log=e((B, k), torch.int64), status=torch.zeros((CSD_STATUS_WORDS,), dtype=torch.int32, device=device),
             workspace=e((nbytes,), torch.uint8))
-
-
-def _rows_stride(t: torch.Tensor, what: str) -> int:
-    if t.dim() != 3 or t.stride(2) != 1 or (t.shape[0] > 1 and t.shape[1] > 0 and t.stride(0) != t.shape[1] * t.stride(1)):
-        raise ValueError(what + " must be [B][rows][V] with equally spaced rows and unit element stride")
-    return t.stride(1) if (t.shape[0] * t.shape[1]) > 1 else max(t.shape[2], t.stride(1))
 
 
 def csd_verify_sampled(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft: torch.Tensor, temperature: float,

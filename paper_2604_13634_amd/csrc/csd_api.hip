@@ -67,7 +67,7 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
     uint64_t *log = rej_log ? rej_log : (apply ? (uint64_t *)((char *)workspace + ws.log_off) : nullptr);
 
-    EpilogueArgs a;
+    EpilogueArgs a = {};
     a.logits = logits;
     a.dtype = dtype;
     a.row_stride = row_stride;
@@ -79,8 +79,11 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     a.lambda = lambda;
     a.ocm = ocm;
     a.capacity = capacity;
-    a.partials = partials;
-    a.partials_per_row = plan.partials_per_row;
+    a.n_shards = 1;
+    a.shard_partials[0] = partials;
+    a.shard_per_row[0] = plan.partials_per_row;
+    a.shard_base[0] = 0;
+    a.draft_logit = nullptr;
     a.accept_len = accept_len;
     a.next_token = next_token;
     a.argmax = argmax;
@@ -103,6 +106,88 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
         if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
     }
     return CSD_OK;
+}
+
+size_t csd_verify_shards_workspace_bytes(int B, int k) {
+    if (B < 0 || k < 0 || k > CSD_MAX_K || (int64_t)B * (k + 1) > (int64_t)1 << 24) return 0;
+    return 256 + (((size_t)B * (size_t)k * sizeof(uint64_t) + 255) & ~(size_t)255);
+}
+
+int csd_verify_shards(int n_shards, const csd_row_partial *const *shard_partials, const int *shard_per_row,
+                      const int *shard_base, const float *draft_logit, const int32_t *draft, int B, int k, int V, float tau,
+                      uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+                      int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+                      uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+                      void *stream) {
+    if (!shape_ok(B, k, V, CSD_DTYPE_F32)) return CSD_EINVAL;
+    if (n_shards < 1 || n_shards > CSD_MAX_SHARDS || !shard_partials || !shard_per_row || !shard_base) return CSD_EINVAL;
+    if (is_nan_bits(tau) || (flags & ~CSD_APPLY_UPDATES)) return CSD_EINVAL;
+    if (B == 0) return CSD_OK;
+    if (!accept_len || !next_token || !argmax || !workspace) return CSD_EINVAL;
+    if (k > 0 && (!draft || !draft_logit)) return CSD_EINVAL;
+    if (ocm && !is_pow2(capacity)) return CSD_EINVAL;
+    for (int s = 0; s < n_shards; ++s) {
+        if (!shard_partials[s] || shard_per_row[s] < 1 || shard_base[s] < 0 || shard_base[s] >= V) return CSD_EINVAL;
+        if (!aligned(shard_partials[s], 16)) return CSD_EALIGN;
+    }
+    if (!aligned(workspace, 16) || !aligned(accept_len, 4) || !aligned(next_token, 4) || !aligned(argmax, 4) ||
+        !aligned(draft, 4) || !aligned(draft_logit, 4) || !aligned(row_max, 4) || !aligned(row_sumexp, 4) ||
+        !aligned(ratio, 4) || !aligned(p_draft, 4) || !aligned(rej_log, 8) || !aligned(ocm, 8) || !aligned(status, 4))
+        return CSD_EALIGN;
+    if (workspace_bytes < csd_verify_shards_workspace_bytes(B, k)) return CSD_ENOSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
+    EpilogueArgs a = {};
+    a.logits = nullptr;
+    a.dtype = CSD_DTYPE_F32;
+    a.row_stride = 0;
+    a.draft = draft;
+    a.B = B;
+    a.k = k;
+    a.V = V;
+    a.tau = tau;
+    a.lambda = lambda;
+    a.ocm = ocm;
+    a.capacity = capacity;
+    a.n_shards = n_shards;
+    for (int s = 0; s < n_shards; ++s) {
+        a.shard_partials[s] = shard_partials[s];
+        a.shard_per_row[s] = shard_per_row[s];
+        a.shard_base[s] = shard_base[s];
+    }
+    a.draft_logit = draft_logit;
+    a.accept_len = accept_len;
+    a.next_token = next_token;
+    a.argmax = argmax;
+    a.row_max = row_max;
+    a.row_sumexp = row_sumexp;
+    a.ratio = ratio;
+    a.p_draft = p_draft;
+    a.pos_flags = pos_flags;
+    a.rej_log = rej_log ? rej_log : (apply ? (uint64_t *)((char *)workspace + 256) : nullptr);
+    a.status = status;
+    a.batch_ticket = (uint32_t *)workspace;
+    const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
+    a.apply_updates = update_in_finish ? 1 : 0;
+    if (update_in_finish && launch_zero_ticket(a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
+    if (launch_finish(a, st) != hipSuccess) return CSD_EHIP;
+    if (apply && !update_in_finish) {
+        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess)
+            return CSD_EHIP;
+    }
+    return CSD_OK;
+}
+
+int csd_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
+                           const int32_t *draft, float *draft_logit, void *stream) {
+    if (!shape_ok(B, k, V_shard, dtype) || base < 0 || (int64_t)base + V_shard > (int64_t)CSD_MAX_V) return CSD_EINVAL;
+    if (B == 0 || k == 0) return CSD_OK;
+    if (!logits || !draft || !draft_logit || row_stride < V_shard) return CSD_EINVAL;
+    const size_t esz = (dtype == CSD_DTYPE_F32) ? 4 : 2;
+    if (!aligned(logits, esz) || !aligned(draft, 4) || !aligned(draft_logit, 4)) return CSD_EALIGN;
+    return launch_shard_draft_logits(logits, dtype, row_stride, B, k, V_shard, base, draft, draft_logit,
+                                     (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
 static SampledWorkspace sampled_layout(const StreamPlan &plan, int B, int k, int nseg) {

@@ -259,14 +259,14 @@ __device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t tota
 // takes partials gs, gs+G, ...; a butterfly over the group finishes).  One pass: running maximum gm, its
 // lowest token id t, and S kept relative to gm.  `scale` is the exponent scale the partials were made
 // with (log2e / temperature), as a double holding the float value.  Every lane of the group gets the result.
-__device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
-                                                     int &t, double &S) {
-    gm = -INFINITY;
-    t = 0x7fffffff;
-    S = 0.0;
+// The two halves are separate so that partials of several vocabulary shards (token ids offset by the
+// shard's base) can be accumulated before the one butterfly.
+__device__ __forceinline__ void accumulate_row_partials(const RowPartial *pp, int P, int G, int gs, double scale,
+                                                        int idx_base, float &gm, int &t, double &S) {
     for (int j = gs; j < P; j += G) {
         const RowPartial q = pp[j];
-        if (q.m > gm || (q.m == gm && q.idx < t)) t = q.idx;
+        const int qi = q.idx + idx_base;
+        if (q.m > gm || (q.m == gm && qi < t)) t = qi;
         if (q.s != 0.f) {                                       // then q.m is finite
             const float mn = fmaxf(gm, q.m);
             const double ref = (double)mn * scale;              // exact: two 24-bit significands
@@ -275,6 +275,8 @@ __device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P
         }
         gm = fmaxf(gm, q.m);
     }
+}
+__device__ __forceinline__ void merge_row_partials_across_group(int G, double scale, float &gm, int &t, double &S) {
     for (int x = 1; x < G; x <<= 1) {
         const float om = xchg_f(gm, x);
         const int ot = xchg_i(t, x);
@@ -287,6 +289,14 @@ __device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P
         S = mine + theirs;
         gm = mn;
     }
+}
+__device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
+                                                     int &t, double &S) {
+    gm = -INFINITY;
+    t = 0x7fffffff;
+    S = 0.0;
+    accumulate_row_partials(pp, P, G, gs, scale, 0, gm, t, S);
+    merge_row_partials_across_group(G, scale, gm, t, S);
 }
 
 // The tail of a step: the workgroup that draws the last of gridDim.x tickets applies the step's log of n

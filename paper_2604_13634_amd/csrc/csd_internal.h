@@ -53,8 +53,12 @@ struct EpilogueArgs {
     uint32_t lambda;
     uint64_t *ocm;           // NULL: no memory
     uint64_t capacity;
-    const RowPartial *partials;
-    int partials_per_row;
+    // row partials: n_shards vocabulary shards (1 for csd_verify), shard s covering token ids from shard_base[s]
+    int n_shards;
+    const RowPartial *shard_partials[CSD_MAX_SHARDS];
+    int shard_per_row[CSD_MAX_SHARDS];
+    int shard_base[CSD_MAX_SHARDS];
+    const float *draft_logit;  // [B][k] logit of each draft token when the logits are not at hand (shards), else NULL
     int32_t *accept_len;
     int32_t *next_token;
     int32_t *argmax;
@@ -138,6 +142,9 @@ hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
                                uint32_t *batch_ticket, hipStream_t stream);
 hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
+hipError_t launch_zero_ticket(uint32_t *ticket, hipStream_t stream);
+hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
+                                     const int32_t *draft, float *draft_logit, hipStream_t stream);
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream);
 hipError_t launch_ocm_reset(uint64_t *ocm, uint64_t capacity, hipStream_t stream);

@@ -48,21 +48,38 @@ __device__ __forceinline__ u32x4 load_chunk_guarded(const char *row, int ch, int
     return q;
 }
 
+// the same for the streaming pass: non-temporal, the row is not read again by this kernel
+template <int DT>
+__device__ __forceinline__ u32x4 stream_chunk_guarded(const char *row, int ch, int nfull, int tail) {
+    using C = Chunk<DT>;
+    u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
+    if (ch < nfull) q = __builtin_nontemporal_load((const u32x4 *)row + ch);
+    else if (ch == nfull && tail > 0) q = C::load_ragged(row, nfull * C::E, tail);
+    return q;
+}
+
 // residual weights of one chunk: w = max(0, p - q), or p itself for the bonus row (use_q false)
 template <int DT>
-__device__ __forceinline__ void chunk_weights(const char *prow, const char *qrow, bool use_q, int ch, int nfull, int tail,
-                                              float scale, const DrawRow &r, float (&w)[Chunk<DT>::E]) {
+__device__ __forceinline__ void weights_of(const u32x4 &cp, const u32x4 &cq, bool use_q, float scale, const DrawRow &r,
+                                           float (&w)[Chunk<DT>::E]) {
     using C = Chunk<DT>;
     float x[C::E];
-    C::unpack(load_chunk_guarded<DT>(prow, ch, nfull, tail), x);
+    C::unpack(cp, x);
 #pragma unroll
     for (int j = 0; j < C::E; ++j) w[j] = prob_of(x[j], scale, r.cp, r.fp);
     if (use_q) {
         float y[C::E];
-        C::unpack(load_chunk_guarded<DT>(qrow, ch, nfull, tail), y);
+        C::unpack(cq, y);
 #pragma unroll
         for (int j = 0; j < C::E; ++j) w[j] = __builtin_fmaxf(__fsub_rn(w[j], prob_of(y[j], scale, r.cq, r.fq)), 0.f);
     }
+}
+template <int DT>
+__device__ __forceinline__ void chunk_weights(const char *prow, const char *qrow, bool use_q, int ch, int nfull, int tail,
+                                              float scale, const DrawRow &r, float (&w)[Chunk<DT>::E]) {
+    const u32x4 cp = load_chunk_guarded<DT>(prow, ch, nfull, tail);
+    const u32x4 cq = use_q ? load_chunk_guarded<DT>(qrow, ch, nfull, tail) : cp;
+    weights_of<DT>(cp, cq, use_q, scale, r, w);
 }
 
 // exclusive prefix sum over the 64 lanes, in double; `total` = the wave's sum, the same value in every lane
@@ -172,17 +189,29 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
     const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
     const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
     const int seg0 = (blockIdx.y * kSegBlockWaves + wave) * kSegsPerWave;
-    for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; ++s) {
-        float sum = 0.f;
+    // two segments at a time: all their loads (2 x kSegLoads per tensor) are issued before any arithmetic
+    for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; s += 2) {
+        constexpr int N = 2 * kSegLoads;
+        u32x4 qp[N], qq[N];
 #pragma unroll
-        for (int u = 0; u < kSegLoads; ++u) {
-            float w[C::E];
-            chunk_weights<DT>(prow, qrow, use_q, s * kSegChunks + u * kWaveSize + lane, nfull, tail, a.scale, r, w);
-#pragma unroll
-            for (int e = 0; e < C::E; ++e) sum += w[e];
+        for (int u = 0; u < N; ++u) {
+            const int ch = s * kSegChunks + u * kWaveSize + lane;       // segment s+1 follows segment s in memory
+            qp[u] = stream_chunk_guarded<DT>(prow, ch, nfull, tail);
+            if (use_q) qq[u] = stream_chunk_guarded<DT>(qrow, ch, nfull, tail);
         }
-        sum = wave_allreduce_f(sum, AddF());
-        if (lane == 0) a.segsum[(int64_t)j * a.nseg + s] = sum;
+        float sum[2] = {0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            float w[C::E];
+            weights_of<DT>(qp[u], qq[u], use_q, a.scale, r, w);
+#pragma unroll
+            for (int e = 0; e < C::E; ++e) sum[u / kSegLoads] += w[e];
+        }
+        const float s0 = wave_allreduce_f(sum[0], AddF()), s1 = wave_allreduce_f(sum[1], AddF());
+        if (lane == 0) {
+            a.segsum[(int64_t)j * a.nseg + s] = s0;
+            if (s + 1 < a.nseg) a.segsum[(int64_t)j * a.nseg + s + 1] = s1;
+        }
     }
 }
 

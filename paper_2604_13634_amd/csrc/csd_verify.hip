@@ -179,7 +179,7 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
 // ---------------------------------------------------------------------------------------------------
 // Phase 2: one wave, one sequence (all 64 lanes active on entry).
 __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, int lane) {
-    const int k = a.k, K1 = a.k + 1, P = a.partials_per_row;
+    const int k = a.k, K1 = a.k + 1;
     const bool is_pos = lane < k;
 
     // draft token and its logit first: independent of the partials, so the latencies overlap
@@ -189,7 +189,9 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     if (is_pos) {
         d = a.draft[(int64_t)b * k + lane];
         valid = (d >= 0) && (d < a.V);
-        if (valid) zd = load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
+        if (valid)
+            zd = a.draft_logit ? a.draft_logit[(int64_t)b * k + lane]
+                               : load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
     }
 
     // ---- combine the partials: G lanes share a row, then a butterfly inside each group of G
@@ -197,11 +199,14 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     while (2 * G * K1 <= kWaveSize) G *= 2;
     const int grow = lane / G, gs = lane & (G - 1);
     const bool active = grow < K1;
-    const RowPartial *pp = a.partials + ((int64_t)b * K1 + (active ? grow : 0)) * P;
-    float gm;
-    int t;
-    double S;
-    combine_row_partials(pp, P, G, gs, kLog2eD, gm, t, S);
+    const int64_t prow = (int64_t)b * K1 + (active ? grow : 0);
+    float gm = -INFINITY;
+    int t = 0x7fffffff;
+    double S = 0.0;
+    for (int s = 0; s < a.n_shards; ++s)
+        accumulate_row_partials(a.shard_partials[s] + prow * a.shard_per_row[s], a.shard_per_row[s], G, gs, kLog2eD,
+                                a.shard_base[s], gm, t, S);
+    merge_row_partials_across_group(G, kLog2eD, gm, t, S);
     if (active && gs == 0) {
         const int64_t row = (int64_t)b * K1 + grow;
         a.argmax[row] = t;
@@ -337,6 +342,35 @@ hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const 
     else
         hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, src, V, plan.nsplit, partials,
                            batch_ticket);
+    return hipGetLastError();
+}
+
+namespace {
+__global__ void zero_ticket_kernel(uint32_t *ticket) { __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// the logit of every draft token this vocabulary shard owns (ids in [base, base + V_shard)); others untouched
+__global__ void shard_draft_logits_kernel(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
+                                          const int32_t *__restrict__ draft, float *__restrict__ draft_logit) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= (int64_t)B * k) return;
+    const int64_t b = o / k, i = o - b * k;
+    const int64_t local = (int64_t)draft[o] - base;
+    if (local < 0 || local >= V_shard) return;
+    draft_logit[o] = load_logit(logits, dtype, (b * (k + 1) + i) * row_stride + local);
+}
+}  // namespace
+
+hipError_t launch_zero_ticket(uint32_t *ticket, hipStream_t stream) {
+    hipLaunchKernelGGL(zero_ticket_kernel, dim3(1), dim3(1), 0, stream, ticket);
+    return hipGetLastError();
+}
+
+hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
+                                     const int32_t *draft, float *draft_logit, hipStream_t stream) {
+    const int64_t n = (int64_t)B * k;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(shard_draft_logits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, logits, dtype,
+                       row_stride, B, k, V_shard, base, draft, draft_logit);
     return hipGetLastError();
 }
 

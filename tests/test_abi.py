@@ -99,4 +99,21 @@ def test_argument_errors_are_synchronous_and_enqueue_nothing():
     assert lib.csd_ocm_export(P(good), 1024, None, None, 5, P(good), None) == b.CSD_EINVAL
     assert lib.csd_ocm_export(P(good), 1024, P(good), P(good), 5, None, None) == b.CSD_EINVAL
     assert lib.csd_ocm_export(P(good), 1024, P(good), P(good + 2), 5, P(good), None) == b.CSD_EALIGN
+    assert lib.csd_verify_shards(0, None, None, None, None, None, 2, 3, 1000, 0.3, 2, None, 0, 0, None, None, None, None, None,
+                                 None, None, None, None, None, None, 0, None) == b.CSD_EINVAL
+    assert lib.csd_verify_shards(9, P(good), P(good), P(good), P(good), P(good), 2, 3, 1000, 0.3, 2, None, 0, 0, P(good),
+                                 P(good), P(good), None, None, None, None, None, None, None, P(good), 4096, None) == b.CSD_EINVAL
+    assert b.csd_verify_shards_workspace_bytes(256, 4) >= 256 + 256 * 4 * 8 and b.csd_verify_shards_workspace_bytes(-1, 4) == 0
+    assert lib.csd_shard_draft_logits(None, 0, 100, 2, 3, 100, 0, P(good), P(good), None) == b.CSD_EINVAL
+    assert lib.csd_shard_draft_logits(P(good), 0, 99, 2, 3, 100, 0, P(good), P(good), None) == b.CSD_EINVAL
+    assert lib.csd_verify_sampled_workspace_bytes(2, 3, 1000, 0) > 0
+    assert lib.csd_verify_sampled(P(good), P(good), 0, 1000, 1000, P(good), 2, 3, 1000, 0.0, P(good), P(good), 0.3, 2, None, 0,
+                                  0, P(good), P(good), None, None, None, None, None, None, None, None, None, P(good), 1 << 20,
+                                  None) == b.CSD_EINVAL                                   # temperature must be positive
+    assert lib.csd_verify_sampled(P(good), P(good), 0, 1000, 999, P(good), 2, 3, 1000, 1.0, P(good), P(good), 0.3, 2, None, 0,
+                                  0, P(good), P(good), None, None, None, None, None, None, None, None, None, P(good), 1 << 20,
+                                  None) == b.CSD_EINVAL                                   # draft stride below V
+    assert lib.csd_verify_sampled(P(good), P(good), 0, 1000, 1000, P(good), 2, 3, 1000, 1.0, P(good), P(good), 0.3, 2, None, 0,
+                                  0, P(good), P(good), None, None, None, None, None, None, None, None, None, P(good), 16,
+                                  None) == b.CSD_ENOSPACE
     assert b.csd_strerror(b.CSD_ENOSPACE) == "workspace too small"

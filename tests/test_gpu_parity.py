@@ -517,6 +517,38 @@ def test_row_partials_combine_to_the_row_statistics(dtype):
         assert tot == pytest.approx(S[r], rel=1e-5)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_verify_from_vocabulary_shards(dtype):
+    """The vocabulary cut into three uneven shards, each reduced on its own (row partials + the logits of the
+    draft tokens it owns), then one csd_verify_shards call: same step as the oracle on the whole rows."""
+    cfg = CONFIGS[2] if dtype == "bf16" else CONFIGS[3]
+    w = Workload(cfg, V=30008, B=24, n_pairs=200)
+    cfg = w.cfg
+    cuts = [0, 8199, 21003, cfg.V]                     # ragged shard widths: padded row pitches
+    orc = O.CSDOracle()
+    ocm = csd.new_ocm(1 << 12)
+    prior = _prior_from_pairs(w, cfg.lam, n=100)
+    orc.ocm_update(*prior)
+    csd.csd_ocm_update(ocm, torch.tensor([(d << 20) | t for d, t in prior[0]], dtype=torch.int64, device="cuda"),
+                       torch.tensor(prior[1], dtype=torch.int32, device="cuda"))
+    bf = None
+    for step in range(6):
+        z, draft = w.step(step)
+        dt = torch.from_numpy(draft).cuda()
+        zd = torch.full((cfg.B, cfg.k), float("nan"), dtype=torch.float32, device="cuda")
+        parts = []
+        for lo, hi in zip(cuts[:-1], cuts[1:]):
+            shard = to_device_logits(np.ascontiguousarray(z[..., lo:hi]))
+            parts.append(csd.csd_row_partials(shard))
+            csd.csd_shard_draft_logits(shard, lo, dt, zd)
+        bf = csd.csd_verify_shards(parts, cuts[:-1], zd, dt, cfg.V, cfg.tau, cfg.lam, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=cfg.lam)
+        compare_step(res, bf, "shards step %d" % step)
+        compare_table(ocm, orc, "shards step %d" % step)
+    assert int(bf.status[csd.CSD_STATUS_RESCUED]) > 0
+
+
 def test_workspace_needs_no_initialisation_and_is_reusable_across_shapes():
     """One workspace, full of garbage at first, serves calls of different shapes back to back."""
     rng = np.random.default_rng(41)
