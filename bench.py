@@ -41,7 +41,8 @@ COPY_BYTES = 1 << 30           # the calibration copy moves 1 GiB in and 1 GiB o
 def kernel_fingerprint() -> str:
     """Hash of the streaming kernel's source and build flags: stored counter readings apply to one version only."""
     h = hashlib.sha256()
-    for rel in ("paper_2604_13634_amd/csrc/csd_verify.hip", "paper_2604_13634_amd/csrc/csd_device.h",
+    for rel in ("paper_2604_13634_amd/csrc/csd_verify.hip", "paper_2604_13634_amd/csrc/csd_sampled.hip",
+                "paper_2604_13634_amd/csrc/csd_device.h",
                 "paper_2604_13634_amd/csrc/csd_internal.h", "paper_2604_13634_amd/build.py"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
@@ -61,30 +62,34 @@ def read_counter(path: str, counter: str):
     return out
 
 
-def ingest_pmc(fetch_path: str, write_path: str, workload: str) -> int:
-    """Scale FETCH_SIZE / WRITE_SIZE of the streaming kernel by what the same counters read for the 1 GiB copy."""
+def ingest_pmc(fetch_path: str, write_path: str, workload: str, kernels=(STREAM_KERNEL,)) -> int:
+    """Scale FETCH_SIZE / WRITE_SIZE of the named kernels by what the same counters read for the 1 GiB copy."""
     rec = {}
     if os.path.exists(TRAFFIC_FILE):
         with open(TRAFFIC_FILE) as f:
             rec = json.load(f)
-    ent = {"kernel": STREAM_KERNEL, "kernel_fingerprint": kernel_fingerprint(), "copy_bytes_each_way": COPY_BYTES}
-    total = 0.0
-    for name, path in (("FETCH_SIZE", fetch_path), ("WRITE_SIZE", write_path)):
-        per_kernel = read_counter(path, name)
-        stream = [v for k, vals in per_kernel.items() if STREAM_KERNEL in k for v in vals]
-        # the calibration copies are the only launches of torch's elementwise copy kernel on 2^30 bytes:
-        # take the kernel whose name mentions a copy and whose reading is largest
-        copies = [v for k, vals in per_kernel.items() if "copy" in k.lower() or "Copy" in k for v in vals]
-        if not stream or not copies:
-            print("bench.py: no %s readings for the streaming kernel or the copy in %s" % (name, path), file=sys.stderr)
-            return 1
-        copy_read = max(copies)
-        unit = COPY_BYTES / copy_read                      # bytes per counter unit on this machine
-        mean = sum(stream) / len(stream)
-        ent[name] = {"stream_mean_reading": mean, "stream_launches": len(stream), "copy_reading": copy_read,
-                     "bytes_per_unit": unit, "bytes_per_launch": mean * unit}
-        total += mean * unit
-    ent["hbm_bytes_per_launch"] = total
+    ent = {"kernel": kernels[0], "kernel_fingerprint": kernel_fingerprint(), "copy_bytes_each_way": COPY_BYTES, "kernels": {}}
+    for kname in kernels:
+        kent = {}
+        total = 0.0
+        for name, path in (("FETCH_SIZE", fetch_path), ("WRITE_SIZE", write_path)):
+            per_kernel = read_counter(path, name)
+            stream = [v for k, vals in per_kernel.items() if kname in k for v in vals]
+            # the calibration copies are the largest launches of a copy kernel in the run
+            copies = [v for k, vals in per_kernel.items() if "copy" in k.lower() for v in vals]
+            if not stream or not copies:
+                print("bench.py: no %s readings for %s or the copy in %s" % (name, kname, path), file=sys.stderr)
+                return 1
+            copy_read = max(copies)
+            unit = COPY_BYTES / copy_read                      # bytes per counter unit on this machine
+            mean = sum(stream) / len(stream)
+            kent[name] = {"stream_mean_reading": mean, "stream_launches": len(stream), "copy_reading": copy_read,
+                          "bytes_per_unit": unit, "bytes_per_launch": mean * unit}
+            total += mean * unit
+        kent["hbm_bytes_per_launch"] = total
+        ent["kernels"][kname] = kent
+    first = ent["kernels"][kernels[0]]
+    ent["FETCH_SIZE"], ent["WRITE_SIZE"], ent["hbm_bytes_per_launch"] = first["FETCH_SIZE"], first["WRITE_SIZE"], first["hbm_bytes_per_launch"]
     rec[workload] = ent
     with open(TRAFFIC_FILE, "w") as f:
         json.dump(rec, f, indent=1, sort_keys=True)
@@ -108,6 +113,8 @@ def bench_sampled(args, cfg) -> int:
     w = SampledWorkload(cfg)
     step_bytes = (cfg.rows + cfg.B * cfg.k) * cfg.V * cfg.itemsize
     n_ring = max(4, int(math.ceil(args.ring_bytes / step_bytes)))
+    if args.pmc_run:
+        n_ring = 4
     ring = []
     for s in range(n_ring):
         zp, zq, d, ua, ud = w.sampled_step(s, threads=args.gen_threads)
@@ -122,13 +129,23 @@ def bench_sampled(args, cfg) -> int:
         zp, zq, d, ua, ud = ring[i % n_ring]
         csd.csd_verify_sampled(zp, zq, d, args.temperature, ua, ud, cfg.tau, cfg.lam, ocm, buffers=bf)
 
+    if args.pmc_run:
+        for i in range(10):
+            step(i)
+        src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
+        src.random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("pmc-run done: 10 csd_verify_sampled steps of %s, 3 copies of %d bytes" % (cfg.name, COPY_BYTES))
+        return 0
     for i in range(args.warmup):
         step(i)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
-    drawn = 0
     for i in range(args.steps):
         step(args.warmup + i)
     e1.record()
@@ -181,6 +198,9 @@ def main() -> int:
     from gen import CONFIGS, Workload
     cfg = CONFIGS[args.config]
     if args.ingest_pmc:
+        if args.path == "sampled":
+            return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name + "+sampled",
+                              (STREAM_KERNEL, "residual_segments_kernel"))
         return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name)
 
     import numpy as np
