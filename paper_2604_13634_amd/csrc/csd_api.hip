@@ -79,6 +79,7 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
     a.lambda = lambda;
     a.ocm = ocm;
     a.capacity = capacity;
+    a.sharded = 0;
     a.n_shards = 1;
     a.shard_partials[0] = partials;
     a.shard_per_row[0] = plan.partials_per_row;
@@ -150,6 +151,7 @@ int csd_verify_shards(int n_shards, const csd_row_partial *const *shard_partials
     a.lambda = lambda;
     a.ocm = ocm;
     a.capacity = capacity;
+    a.sharded = 1;
     a.n_shards = n_shards;
     for (int s = 0; s < n_shards; ++s) {
         a.shard_partials[s] = shard_partials[s];

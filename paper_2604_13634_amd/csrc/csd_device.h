@@ -109,7 +109,7 @@ __device__ inline bool ocm_add(uint64_t *ocm, uint64_t capacity, uint64_t key, u
 // compare-and-swap chain per DISTINCT pair; the distinct pairs are then compacted so that all of them
 // go to the table side by side (one round of global atomics per kApplyThreads distinct pairs) instead of
 // slot by slot.
-constexpr int kApplyThreads = 256;
+constexpr int kApplyThreads = 1024;               // also the finish kernels' workgroup: 16 sequences each
 constexpr int kApplyBatch = 1024;                 // entries merged at a time
 constexpr int kApplySlots = 2 * kApplyBatch;      // LDS table never fills
 constexpr int kApplyPerThread = kApplyBatch / kApplyThreads;
@@ -255,48 +255,109 @@ __device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t tota
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Combine the P partials of one row, shared by a group of G lanes (G a power of two; lane gs of the group
-// takes partials gs, gs+G, ...; a butterfly over the group finishes).  One pass: running maximum gm, its
-// lowest token id t, and S kept relative to gm.  `scale` is the exponent scale the partials were made
-// with (log2e / temperature), as a double holding the float value.  Every lane of the group gets the result.
-// The two halves are separate so that partials of several vocabulary shards (token ids offset by the
-// shard's base) can be accumulated before the one butterfly.
-__device__ __forceinline__ void accumulate_row_partials(const RowPartial *pp, int P, int G, int gs, double scale,
-                                                        int idx_base, float &gm, int &t, double &S) {
-    for (int j = gs; j < P; j += G) {
-        const RowPartial q = pp[j];
-        const int qi = q.idx + idx_base;
-        if (q.m > gm || (q.m == gm && qi < t)) t = qi;
-        if (q.s != 0.f) {                                       // then q.m is finite
-            const float mn = fmaxf(gm, q.m);
-            const double ref = (double)mn * scale;              // exact: two 24-bit significands
-            const double keep = (S != 0.0) ? S * exp2((double)gm * scale - ref) : 0.0;
-            S = keep + (double)q.s * exp2((double)q.cref - ref);
+// Combine the partials of one row, shared by a group of G lanes (G a power of two; lane gs of the group
+// takes partials gs, gs+G, ...).  Two passes over the partials (the second finds them in cache): first the
+// maximum m and its lowest token id t, a butterfly over the group; then S = sum s_j 2^(cref_j - m*scale)
+// against that one maximum - independent terms in double - and a second butterfly.  `scale` is the exponent
+// scale the partials were made with (log2e / temperature), as a double holding the float value.  A row
+// may come as several sets of partials (vocabulary shards, token ids offset by the shard's base): the
+// `*_pass` functions take one set each, the `*_merge` functions finish a pass across the group.
+// Both passes read four partials per lane at a time, all four loads issued before any is used: a plain
+// loop would pay one memory latency per partial.
+constexpr int kPartialBatch = 4;
+__device__ __forceinline__ RowPartial empty_partial() {
+    RowPartial q;
+    q.m = -INFINITY;
+    q.cref = 0.f;
+    q.s = 0.f;
+    q.idx = 0x7fffffff;
+    return q;
+}
+__device__ __forceinline__ void partials_max_pass(const RowPartial *pp, int P, int G, int gs, int idx_base, float &gm, int &t) {
+    for (int j0 = gs; j0 < P; j0 += kPartialBatch * G) {
+        RowPartial q[kPartialBatch];
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) q[u] = (j0 + u * G < P) ? pp[j0 + u * G] : empty_partial();
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) {
+            const int qi = (q[u].idx == 0x7fffffff) ? q[u].idx : q[u].idx + idx_base;
+            if (q[u].m > gm || (q[u].m == gm && qi < t)) t = qi;
+            gm = fmaxf(gm, q[u].m);
         }
-        gm = fmaxf(gm, q.m);
     }
 }
-__device__ __forceinline__ void merge_row_partials_across_group(int G, double scale, float &gm, int &t, double &S) {
+__device__ __forceinline__ void partials_max_merge(int G, float &gm, int &t) {
     for (int x = 1; x < G; x <<= 1) {
         const float om = xchg_f(gm, x);
         const int ot = xchg_i(t, x);
-        const double oS = xchg_d(S, x);
         if (om > gm || (om == gm && ot < t)) t = ot;
-        const float mn = fmaxf(gm, om);
-        const double ref = (double)mn * scale;
-        const double mine = (S != 0.0) ? S * exp2((double)gm * scale - ref) : 0.0;
-        const double theirs = (oS != 0.0) ? oS * exp2((double)om * scale - ref) : 0.0;
-        S = mine + theirs;
-        gm = mn;
+        gm = fmaxf(gm, om);
     }
+}
+__device__ __forceinline__ void partials_sum_pass(const RowPartial *pp, int P, int G, int gs, double mref, double &S) {
+    for (int j0 = gs; j0 < P; j0 += kPartialBatch * G) {
+        RowPartial q[kPartialBatch];
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) q[u] = (j0 + u * G < P) ? pp[j0 + u * G] : empty_partial();
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) {
+            // the exponent difference is exact in double; as a float it is off by at most 2^-24 of itself, which
+            // only matters for terms too small to count, so the hardware exp2 serves
+            if (q[u].s != 0.f) S += (double)q[u].s * (double)__builtin_amdgcn_exp2f((float)((double)q[u].cref - mref));
+        }
+    }
+}
+__device__ __forceinline__ void partials_sum_merge(int G, double &S) {
+    for (int x = 1; x < G; x <<= 1) S += xchg_d(S, x);
+}
+// A row whose partials fit NB registers per lane (the usual case) is read ONCE, all loads in flight together.
+template <int NB>
+__device__ __forceinline__ void combine_row_partials_once(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
+                                                          int &t, double &S) {
+    RowPartial q[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) q[u] = (gs + u * G < P) ? pp[gs + u * G] : empty_partial();
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        if (q[u].m > gm || (q[u].m == gm && q[u].idx < t)) t = q[u].idx;
+        gm = fmaxf(gm, q[u].m);
+    }
+    partials_max_merge(G, gm, t);
+    const double mref = (double)gm * scale;                    // exact: two 24-bit significands
+#pragma unroll
+    for (int u = 0; u < NB; ++u)
+        if (q[u].s != 0.f) S += (double)q[u].s * (double)__builtin_amdgcn_exp2f((float)((double)q[u].cref - mref));
+    partials_sum_merge(G, S);
 }
 __device__ __forceinline__ void combine_row_partials(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
                                                      int &t, double &S) {
     gm = -INFINITY;
     t = 0x7fffffff;
     S = 0.0;
-    accumulate_row_partials(pp, P, G, gs, scale, 0, gm, t, S);
-    merge_row_partials_across_group(G, scale, gm, t, S);
+    const int per_lane = (P + G - 1) / G;                      // wave-uniform
+    if (per_lane <= 2) return combine_row_partials_once<2>(pp, P, G, gs, scale, gm, t, S);
+    if (per_lane <= 4) return combine_row_partials_once<4>(pp, P, G, gs, scale, gm, t, S);
+    if (per_lane <= 9) return combine_row_partials_once<9>(pp, P, G, gs, scale, gm, t, S);
+    if (per_lane <= 16) return combine_row_partials_once<16>(pp, P, G, gs, scale, gm, t, S);
+    partials_max_pass(pp, P, G, gs, 0, gm, t);
+    partials_max_merge(G, gm, t);
+    partials_sum_pass(pp, P, G, gs, (double)gm * scale, S);     // m * scale is exact: two 24-bit significands
+    partials_sum_merge(G, S);
+}
+
+// Status counters of a step are summed per workgroup in LDS and leave it as one global atomic per counter:
+// hundreds of waves adding to the same four words cost the finish kernels several microseconds.
+struct BlockCounters {
+    unsigned int v[CSD_STATUS_WORDS];
+};
+__device__ __forceinline__ void block_counters_clear(BlockCounters &c) {     // every thread; contains a barrier
+    if (threadIdx.x < CSD_STATUS_WORDS) c.v[threadIdx.x] = 0;
+    __syncthreads();
+}
+__device__ __forceinline__ void block_counters_flush(BlockCounters &c, uint32_t *status) {   // every thread; barrier
+    __syncthreads();
+    if (status != nullptr && threadIdx.x < CSD_STATUS_WORDS && c.v[threadIdx.x] != 0)
+        atomicAdd(&status[threadIdx.x], c.v[threadIdx.x]);
 }
 
 // The tail of a step: the workgroup that draws the last of gridDim.x tickets applies the step's log of n

@@ -54,6 +54,7 @@ struct EpilogueArgs {
     uint64_t *ocm;           // NULL: no memory
     uint64_t capacity;
     // row partials: n_shards vocabulary shards (1 for csd_verify), shard s covering token ids from shard_base[s]
+    int sharded;               // 1: csd_verify_shards (several partial sets, draft logits from draft_logit)
     int n_shards;
     const RowPartial *shard_partials[CSD_MAX_SHARDS];
     int shard_per_row[CSD_MAX_SHARDS];

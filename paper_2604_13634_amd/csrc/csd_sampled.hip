@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
 
 // ---------------------------------------------------------------------------------------------------
 // Launch 5: the loop itself.  One wave per sequence.
-__device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, int lane) {
+__device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters) {
     const int k = a.k, K1 = a.k + 1;
     const bool is_pos = lane < k;
     int d = -1, t = -1;
@@ -366,21 +366,22 @@ __device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, in
     if (lane == 0) {
         a.accept_len[b] = n;
         a.next_token[b] = next;
-        if (a.status) {
-            if (m_bad) atomicAdd(&a.status[CSD_STATUS_BAD_DRAFT], (uint32_t)__builtin_popcountll(m_bad));
-            if (m_rescued) atomicAdd(&a.status[CSD_STATUS_RESCUED], (uint32_t)__builtin_popcountll(m_rescued));
-            if (m_counted) atomicAdd(&a.status[CSD_STATUS_COUNTED], (uint32_t)__builtin_popcountll(m_counted));
-            if (n) atomicAdd(&a.status[CSD_STATUS_ACCEPTED], (uint32_t)n);
-        }
+        if (m_bad) atomicAdd(&counters.v[CSD_STATUS_BAD_DRAFT], (unsigned int)__builtin_popcountll(m_bad));
+        if (m_rescued) atomicAdd(&counters.v[CSD_STATUS_RESCUED], (unsigned int)__builtin_popcountll(m_rescued));
+        if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
+        if (n) atomicAdd(&counters.v[CSD_STATUS_ACCEPTED], (unsigned int)n);
     }
 }
 
 __global__ __launch_bounds__(kApplyThreads) void sampled_finish_kernel(SampledArgs a) {
     __shared__ ApplyLds lds;
+    __shared__ BlockCounters counters;
     __shared__ int verdict;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (b < a.B) sampled_sequence(a, b, lane);
+    block_counters_clear(counters);
+    if (b < a.B) sampled_sequence(a, b, lane, counters);
+    block_counters_flush(counters, a.status);
     if (!a.apply_updates) return;
     apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
 }

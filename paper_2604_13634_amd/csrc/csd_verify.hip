@@ -178,7 +178,9 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
 
 // ---------------------------------------------------------------------------------------------------
 // Phase 2: one wave, one sequence (all 64 lanes active on entry).
-__device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, int lane) {
+// SHARDED: the row partials come as several sets (vocabulary shards) and the draft logits as an array.
+template <bool SHARDED>
+__device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, int lane, BlockCounters &counters) {
     const int k = a.k, K1 = a.k + 1;
     const bool is_pos = lane < k;
 
@@ -190,8 +192,8 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
         d = a.draft[(int64_t)b * k + lane];
         valid = (d >= 0) && (d < a.V);
         if (valid)
-            zd = a.draft_logit ? a.draft_logit[(int64_t)b * k + lane]
-                               : load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
+            zd = SHARDED ? a.draft_logit[(int64_t)b * k + lane]
+                         : load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
     }
 
     // ---- combine the partials: G lanes share a row, then a butterfly inside each group of G
@@ -203,10 +205,17 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     float gm = -INFINITY;
     int t = 0x7fffffff;
     double S = 0.0;
-    for (int s = 0; s < a.n_shards; ++s)
-        accumulate_row_partials(a.shard_partials[s] + prow * a.shard_per_row[s], a.shard_per_row[s], G, gs, kLog2eD,
-                                a.shard_base[s], gm, t, S);
-    merge_row_partials_across_group(G, kLog2eD, gm, t, S);
+    if (!SHARDED) {
+        combine_row_partials(a.shard_partials[0] + prow * a.shard_per_row[0], a.shard_per_row[0], G, gs, kLog2eD, gm, t, S);
+    } else {
+        for (int s = 0; s < a.n_shards; ++s)
+            partials_max_pass(a.shard_partials[s] + prow * a.shard_per_row[s], a.shard_per_row[s], G, gs, a.shard_base[s], gm, t);
+        partials_max_merge(G, gm, t);
+        const double mref = (double)gm * kLog2eD;
+        for (int s = 0; s < a.n_shards; ++s)
+            partials_sum_pass(a.shard_partials[s] + prow * a.shard_per_row[s], a.shard_per_row[s], G, gs, mref, S);
+        partials_sum_merge(G, S);
+    }
     if (active && gs == 0) {
         const int64_t row = (int64_t)b * K1 + grow;
         a.argmax[row] = t;
@@ -265,12 +274,10 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     if (lane == 0) {
         a.accept_len[b] = n;
         a.next_token[b] = next;
-        if (a.status) {
-            if (m_bad) atomicAdd(&a.status[CSD_STATUS_BAD_DRAFT], (uint32_t)__builtin_popcountll(m_bad));
-            if (m_rescued) atomicAdd(&a.status[CSD_STATUS_RESCUED], (uint32_t)__builtin_popcountll(m_rescued));
-            if (m_counted) atomicAdd(&a.status[CSD_STATUS_COUNTED], (uint32_t)__builtin_popcountll(m_counted));
-            if (n) atomicAdd(&a.status[CSD_STATUS_ACCEPTED], (uint32_t)n);
-        }
+        if (m_bad) atomicAdd(&counters.v[CSD_STATUS_BAD_DRAFT], (unsigned int)__builtin_popcountll(m_bad));
+        if (m_rescued) atomicAdd(&counters.v[CSD_STATUS_RESCUED], (unsigned int)__builtin_popcountll(m_rescued));
+        if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
+        if (n) atomicAdd(&counters.v[CSD_STATUS_ACCEPTED], (unsigned int)n);
     }
 }
 
@@ -292,12 +299,16 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kerne
     if (lane == 0) partials[((int64_t)row * nsplit + split) * kStreamWaves + wave] = out;   // one 16-byte store
 }
 
+template <bool SHARDED>
 __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
     __shared__ ApplyLds lds;
+    __shared__ BlockCounters counters;
     __shared__ int verdict;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (b < a.B) sequence_epilogue(a, b, lane);      // wave-uniform: a wave takes a sequence or none
+    block_counters_clear(counters);
+    if (b < a.B) sequence_epilogue<SHARDED>(a, b, lane, counters);   // wave-uniform: a wave takes a sequence or none
+    block_counters_flush(counters, a.status);
     if (!a.apply_updates) return;
     apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
 }
@@ -377,7 +388,10 @@ hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_
 hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream) {
     if (a.B == 0) return hipSuccess;
     const dim3 grid((unsigned)((a.B + kFinishWaves - 1) / kFinishWaves));
-    hipLaunchKernelGGL(finish_kernel, grid, dim3(kFinishWaves * kWaveSize), 0, stream, a);
+    if (a.sharded)
+        hipLaunchKernelGGL(finish_kernel<true>, grid, dim3(kFinishWaves * kWaveSize), 0, stream, a);
+    else
+        hipLaunchKernelGGL(finish_kernel<false>, grid, dim3(kFinishWaves * kWaveSize), 0, stream, a);
     return hipGetLastError();
 }
 
