@@ -193,11 +193,20 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
     for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; s += 2) {
         constexpr int N = 2 * kSegLoads;
         u32x4 qp[N], qq[N];
+        if ((s + 2) * kSegChunks <= nfull) {                            // both segments are whole chunks of the row: no guards
 #pragma unroll
-        for (int u = 0; u < N; ++u) {
-            const int ch = s * kSegChunks + u * kWaveSize + lane;       // segment s+1 follows segment s in memory
-            qp[u] = stream_chunk_guarded<DT>(prow, ch, nfull, tail);
-            if (use_q) qq[u] = stream_chunk_guarded<DT>(qrow, ch, nfull, tail);
+            for (int u = 0; u < N; ++u) {
+                const int ch = s * kSegChunks + u * kWaveSize + lane;   // segment s+1 follows segment s in memory
+                qp[u] = __builtin_nontemporal_load((const u32x4 *)prow + ch);
+                if (use_q) qq[u] = __builtin_nontemporal_load((const u32x4 *)qrow + ch);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < N; ++u) {
+                const int ch = s * kSegChunks + u * kWaveSize + lane;
+                qp[u] = stream_chunk_guarded<DT>(prow, ch, nfull, tail);
+                if (use_q) qq[u] = stream_chunk_guarded<DT>(qrow, ch, nfull, tail);
+            }
         }
         float sum[2] = {0.f, 0.f};
 #pragma unroll
@@ -268,10 +277,19 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
         const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
         const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
         int last_tok = -1;
-        for (int u = 0; u < kSegLoads && result < 0; ++u) {
+        u32x4 cp[kSegLoads], cq[kSegLoads];                // the whole segment's loads first: one latency, not four
+#pragma unroll
+        for (int u = 0; u < kSegLoads; ++u) {
+            const int ch = sstar * kSegChunks + u * kWaveSize + lane;
+            cp[u] = load_chunk_guarded<DT>(prow, ch, nfull, tail);
+            cq[u] = use_q ? load_chunk_guarded<DT>(qrow, ch, nfull, tail) : cp[u];
+        }
+#pragma unroll
+        for (int u = 0; u < kSegLoads; ++u) {
+            if (result >= 0) break;
             const int ch = sstar * kSegChunks + u * kWaveSize + lane;
             float w[C::E];
-            chunk_weights<DT>(prow, qrow, use_q, ch, nfull, tail, a.scale, r, w);
+            weights_of<DT>(cp[u], cq[u], use_q, a.scale, r, w);
             double lsum = 0.0;
             int my_last = -1;
 #pragma unroll
