@@ -571,3 +571,38 @@ def test_workspace_needs_no_initialisation_and_is_reusable_across_shapes():
             res = orc.verify_step(z, draft, tau=np.float32(0.05), lam=1)
             compare_step(res, bf, "shape %r rep %d" % ((B, k, V, dt), rep))
     compare_table(ocm, orc)
+
+
+def test_step_replayed_from_a_captured_graph():
+    """A verification step allocates nothing and records only kernel launches, so it can be captured in a
+    graph; several replays, with new inputs copied into the captured buffers and eager work in between,
+    each match the oracle (memory updates included)."""
+    w = Workload(CONFIGS[1], V=12000, B=8)
+    cfg = w.cfg
+    z0, d0 = w.step(0)
+    zt = to_device_logits(z0)
+    dt = torch.from_numpy(d0).cuda()
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    bf = csd.VerifyBuffers.allocate(cfg.B, cfg.k, cfg.V, csd.CSD_DTYPE_BF16)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture, then undo its updates
+        csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm, buffers=bf)
+        csd.csd_ocm_reset(ocm)
+        bf.status.zero_()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm, buffers=bf)
+    for step in range(5):
+        z, d = w.step(step)
+        zt.copy_(to_device_logits(z))
+        dt.copy_(torch.from_numpy(d).cuda())
+        g.replay()
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, d, tau=np.float32(cfg.tau), lam=cfg.lam)
+        compare_step(res, bf, "graph replay %d" % step)
+        compare_table(ocm, orc, "graph replay %d" % step)
+        assert int(csd.csd_ocm_lookup(ocm, torch.tensor([(1 << 20) | 2], dtype=torch.int64, device="cuda"))[0]) >= 0   # eager work between replays

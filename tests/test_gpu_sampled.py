@@ -147,3 +147,30 @@ def test_small_temperature_agrees_with_the_greedy_entry_point():
         rescued += int(s.status[csd.CSD_STATUS_RESCUED])
     assert rescued > 5
     assert csd.decode_ocm(ocm_g) == csd.decode_ocm(ocm_s) and len(csd.decode_ocm(ocm_g)) > 10
+
+
+@pytest.mark.parametrize("B,k,V", [(2200, 4, 520), (3, 31, 1500), (2, 63, 900), (300, 7, 1030)])
+def test_large_batches_and_long_drafts(B, k, V):
+    """More than 8192 draft positions (the separate update launch), k up to the limit (one lane per row in
+    the sequence kernels), several merge batches of the in-kernel update."""
+    rng = np.random.default_rng(B + k)
+    ocm = csd.new_ocm(1 << 13)
+    orc = O.CSDOracle()
+    bf = None
+    heavy_n = 5
+    for step in range(3):
+        zp = (rng.standard_normal((B, k + 1, V)) * 1.5).astype(np.float32)
+        zq = (rng.standard_normal((B, k, V)) * 1.5).astype(np.float32)
+        heavy = rng.integers(0, 40, (B, k + 1, heavy_n))            # few tokens carry the mass: pairs recur
+        np.put_along_axis(zp, heavy, (10 + rng.random((B, k + 1, heavy_n)) * 3).astype(np.float32), axis=-1)
+        np.put_along_axis(zq, heavy[:, :k, ::-1].copy(), (10 + rng.random((B, k, heavy_n)) * 3).astype(np.float32), axis=-1)
+        draft = heavy[:, :k, 0].astype(np.int32)
+        ua, ud = settle_uniforms(zp, zq, draft, 1.0, rng.random((B, k), dtype=np.float32),
+                                 rng.random((B, k + 1), dtype=np.float32), seed=step)
+        bf = csd.csd_verify_sampled(to_device_logits(zp), to_device_logits(zq), torch.from_numpy(draft).cuda(), 1.0,
+                                    torch.from_numpy(ua).cuda(), torch.from_numpy(ud).cuda(), 0.05, 1, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = OS.verify_step_sampled(orc, zp, zq, draft, 1.0, ua, ud, tau=np.float32(0.05), lam=1)
+        compare_sampled_step(res, bf, "B=%d k=%d step %d" % (B, k, step))
+        compare_table(ocm, orc, "B=%d k=%d step %d" % (B, k, step))
+    assert int(bf.status[csd.CSD_STATUS_COUNTED]) == sum(orc.T.values()) > 0
