@@ -188,6 +188,13 @@ def main() -> int:
     ap.add_argument("--path", choices=("greedy", "sampled"), default="greedy",
                     help="greedy: csd_verify (the headline); sampled: csd_verify_sampled at --temperature")
     ap.add_argument("--temperature", type=float, default=1.0)
+    ap.add_argument("--batch", type=int, help="override the workload's B")
+    ap.add_argument("--draft-len", type=int, help="override the workload's k")
+    ap.add_argument("--vocab", type=int, help="override the workload's V")
+    ap.add_argument("--tau", type=float, help="override the gate threshold")
+    ap.add_argument("--lam", type=int, help="override the frequency threshold")
+    ap.add_argument("--graph", action="store_true",
+                    help="greedy path: replay each step from a captured graph instead of launching it (ring capped at 64 steps)")
     ap.add_argument("--pmc-run", action="store_true", help="short run for rocprofv3 --pmc (see module docstring)")
     ap.add_argument("--ingest-pmc", nargs=2, metavar=("FETCH", "WRITE"))
     args = ap.parse_args()
@@ -197,6 +204,11 @@ def main() -> int:
 
     from gen import CONFIGS, Workload
     cfg = CONFIGS[args.config]
+    over = {k: v for k, v in (("B", args.batch), ("k", args.draft_len), ("V", args.vocab), ("tau", args.tau), ("lam", args.lam))
+            if v is not None}
+    if over:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name=cfg.name + "".join("_%s%g" % kv for kv in sorted(over.items())), **over)
     if args.ingest_pmc:
         if args.path == "sampled":
             return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name + "+sampled",
@@ -217,6 +229,8 @@ def main() -> int:
     w = Workload(cfg)
     rows = cfg.rows
     n_ring = max(4, int(math.ceil(args.ring_bytes / cfg.bytes_per_step)))
+    if args.graph:
+        n_ring = min(n_ring, 64)
     if args.pmc_run:
         n_ring, args.steps, args.warmup = 4, 8, 2
 
@@ -239,6 +253,24 @@ def main() -> int:
         ocm = csd.new_ocm(cfg.capacity)
         for i in range(warmup):
             csd.csd_verify(ring_z[i % n_ring], ring_d[i % n_ring], cfg.tau, cfg.lam, ocm, flags, buffers=bf)
+        if args.graph:                                # one captured step per ring slot, replayed in the timed loop
+            torch.cuda.synchronize()
+            graphs = []
+            for j in range(n_ring):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    csd.csd_verify(ring_z[j], ring_d[j], cfg.tau, cfg.lam, ocm, flags, buffers=bf)
+                graphs.append(g)
+            csd.csd_ocm_reset(ocm)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            for i in range(steps):
+                graphs[(warmup + i) % n_ring].replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0, ocm, e0.elapsed_time(e1) / steps
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -310,6 +342,7 @@ def main() -> int:
             "workload": cfg.name, "B": cfg.B, "k": cfg.k, "V": cfg.V, "logits_storage": cfg.dtype,
             "positions_per_step": rows, "draft_positions_per_step": cfg.B * cfg.k,
             "tau": cfg.tau, "lambda": cfg.lam, "ocm_capacity": cfg.capacity, "ocm_updates": "applied",
+            "launch": "graph replay" if args.graph else "two kernel launches per step",
             "ring_steps": n_ring, "ring_bytes": n_ring * cfg.bytes_per_step,
             "positions_per_s_without_ocm_updates": rows * args.steps / elapsed_noupd,
             "ms_per_step_without_ocm_updates": elapsed_noupd / args.steps * 1e3,

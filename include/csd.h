@@ -109,6 +109,9 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  *   tau         gate threshold on p(draft)/p(t*) (inclusive).  tau <= 0: gate always passes;
  *               tau > 1: never passes (strict matching).  NaN is rejected.
  *   lambda      frequency threshold (inclusive).  0: every pair is frequent (gate-only mode).
+ *               UINT32_MAX: no pair ever is - plain speculative decoding that still counts its
+ *               divergences, i.e. the prior-calibration run that fills the memory before deployment
+ *               (Online Correction Memory, phase 1).
  *   ocm         the table, or NULL: no memory (plain strict matching, nothing is updated).
  *   capacity    slots in `ocm`, a power of two >= 1 (ignored when ocm == NULL).
  *   flags       CSD_APPLY_UPDATES or 0.

@@ -174,3 +174,19 @@ def test_large_batches_and_long_drafts(B, k, V):
         compare_sampled_step(res, bf, "B=%d k=%d step %d" % (B, k, step))
         compare_table(ocm, orc, "B=%d k=%d step %d" % (B, k, step))
     assert int(bf.status[csd.CSD_STATUS_COUNTED]) == sum(orc.T.values()) > 0
+
+
+def test_prior_calibration_run_counts_without_rescuing():
+    """Phase 1 of the memory: standard speculative sampling (here at T = 0.6) with the frequency threshold out
+    of reach - nothing is rescued, every first divergence of a sequence is counted; the table it leaves is then
+    the prior of a run with the method's thresholds."""
+    w = SampledWorkload(CONFIGS[1], V=5003, B=32, n_pairs=64)
+    cfg = w.cfg
+    orc, ocm, rescued, counted, rejected = run_sampled_stream(w, range(25), 0.6, lam=2 ** 32 - 1, capacity=1 << 12)
+    assert rescued == 0 and counted > 100
+    # every sequence stops at its first failed acceptance test, so it counts at most one pair per step
+    assert counted <= 25 * cfg.B
+    before = dict(orc.T)
+    orc2, ocm2, rescued2, _, _ = run_sampled_stream(w, range(25, 40), 0.6, lam=2, capacity=1 << 12,
+                                                    prior=(list(before.keys()), list(before.values())))
+    assert rescued2 > 0
