@@ -156,6 +156,10 @@ def new_ocm(capacity: int, device="cuda") -> torch.Tensor:
     return ocm
 
 
+def _current_stream_handle() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
 def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
                ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
                buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True) -> VerifyBuffers:
@@ -167,9 +171,10 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
         raise ValueError("logits must be [B][k+1][V]")
     B, K1, V = logits.shape
     k = K1 - 1
-    if logits.stride(2) != 1 or (B > 1 and logits.stride(0) != K1 * logits.stride(1)):
+    s0, s1, s2 = logits.stride()
+    if s2 != 1 or (B > 1 and s0 != K1 * s1):
         raise ValueError("logits rows must be equally spaced with unit element stride")
-    row_stride = logits.stride(1) if K1 > 1 or B > 1 else max(V, logits.stride(1))
+    row_stride = s1 if K1 > 1 or B > 1 else max(V, s1)
     if draft is not None:
         if draft.dtype != torch.int32 or tuple(draft.shape) != (B, k) or not draft.is_contiguous():
             raise ValueError("draft must be a contiguous int32 [B][k] tensor")
@@ -181,13 +186,22 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
     if ocm is not None and (ocm.dtype != torch.int64 or not ocm.is_contiguous()):
         raise ValueError("ocm must be a contiguous int64 tensor")
     bf = buffers
-    opt = (lambda t: _ptr(t)) if diagnostics else (lambda t: None)
+    # addresses of the outputs are fixed for the life of the buffers: marshal them once
+    cache = bf.__dict__.get("_verify_args")
+    if cache is None:
+        full = (bf.accept_len.data_ptr(), bf.next_token.data_ptr(), bf.argmax.data_ptr(), bf.row_max.data_ptr(),
+                bf.row_sumexp.data_ptr(), bf.ratio.data_ptr(), bf.p_draft.data_ptr(), bf.pos_flags.data_ptr(),
+                bf.rej_log.data_ptr(), bf.status.data_ptr(), bf.workspace.data_ptr(), bf.workspace.numel())
+        lean = full[:3] + (None,) * 6 + full[9:]
+        cache = bf.__dict__["_verify_args"] = (full, lean)
+    outs = cache[0] if diagnostics else cache[1]
+    if stream is None:
+        st = _current_stream_handle()
+    else:
+        st = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
     rc = load_library().csd_verify(
-        _ptr(logits), dt, row_stride, _ptr(draft), B, k, V, float(tau), int(lam) & 0xFFFFFFFF,
-        _ptr(ocm), 0 if ocm is None else ocm.numel(), int(flags),
-        _ptr(bf.accept_len), _ptr(bf.next_token), _ptr(bf.argmax), opt(bf.row_max), opt(bf.row_sumexp),
-        opt(bf.ratio), opt(bf.p_draft), opt(bf.pos_flags), opt(bf.rej_log), _ptr(bf.status),
-        _ptr(bf.workspace), bf.workspace.numel(), _stream(stream))
+        logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
+        None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags, *outs, st or None)
     if rc != CSD_OK:
         raise CsdError(rc, "csd_verify")
     return bf
