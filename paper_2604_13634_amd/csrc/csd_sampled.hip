@@ -74,14 +74,6 @@ __device__ __forceinline__ void weights_of(const u32x4 &cp, const u32x4 &cq, boo
         for (int j = 0; j < C::E; ++j) w[j] = __builtin_fmaxf(__fsub_rn(w[j], prob_of(y[j], scale, r.cq, r.fq)), 0.f);
     }
 }
-template <int DT>
-__device__ __forceinline__ void chunk_weights(const char *prow, const char *qrow, bool use_q, int ch, int nfull, int tail,
-                                              float scale, const DrawRow &r, float (&w)[Chunk<DT>::E]) {
-    const u32x4 cp = load_chunk_guarded<DT>(prow, ch, nfull, tail);
-    const u32x4 cq = use_q ? load_chunk_guarded<DT>(qrow, ch, nfull, tail) : cp;
-    weights_of<DT>(cp, cq, use_q, scale, r, w);
-}
-
 // exclusive prefix sum over the 64 lanes, in double; `total` = the wave's sum, the same value in every lane
 __device__ __forceinline__ double wave_exclusive_scan_d(double v, int lane, double &total) {
     double incl = v;

@@ -22,7 +22,7 @@
 //   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
 //   2^d with |d| <= ulp(c)/2: this is why logits are limited to |z| <= 2^29 (d <= 32, sums stay in range).
 //
-// Kernel 2 - finish (finish_kernel), one wave per sequence, four sequences per workgroup: combine the row
+// Kernel 2 - finish (finish_kernel), one wave per sequence, sixteen sequences per workgroup: combine the row
 // partials (normaliser in double), draft-token ratio and probability (Eq. 3), memory lookup then gate
 // (Algorithm 1), accepted-prefix scan by ballot, emitted token, and the list of divergences to count.
 // Each workgroup then takes a ticket on the batch; the workgroup that draws the last ticket knows that

@@ -606,3 +606,33 @@ def test_step_replayed_from_a_captured_graph():
         compare_step(res, bf, "graph replay %d" % step)
         compare_table(ocm, orc, "graph replay %d" % step)
         assert int(csd.csd_ocm_lookup(ocm, torch.tensor([(1 << 20) | 2], dtype=torch.int64, device="cuda"))[0]) >= 0   # eager work between replays
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_vocabulary_and_smallest_table(dtype):
+    """V = 2^20 (the largest the packed pair allows), with the top token at the very end and a tie across
+    the row; a memory of one slot (every second pair is dropped and reported)."""
+    V = csd.CSD_MAX_V
+    rng = np.random.default_rng(17)
+    z = (rng.standard_normal((2, 2, V)) * 2).astype(np.float32)
+    z[0, 0, V - 1] = 15.0
+    z[0, 0, 3] = 15.0                                   # tie between token 3 and the last token
+    z[0, 1, V - 1] = 14.0
+    z[1, 0, V - 2] = 16.0
+    z[1, 1, 12345] = 16.0
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z).reshape(z.shape)
+    draft = np.array([[V - 1], [V - 2]], dtype=np.int32)
+    ocm = csd.new_ocm(1)
+    orc = O.CSDOracle(capacity=1)
+    bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), 0.3, 0, ocm)
+    torch.cuda.synchronize()
+    res = orc.verify_step(z, draft, tau=np.float32(0.3), lam=0)
+    compare_step(res, bf, "V=2^20")
+    assert bf.argmax.cpu().tolist() == [[3, V - 1], [V - 2, 12345]]
+    assert csd.decode_ocm(ocm) == {(V - 1, 3): 1} == orc.T          # the pair of sequence 0; sequence 1 matched
+    # a second pair finds the single slot taken: dropped, and said so
+    draft2 = np.array([[5], [7]], dtype=np.int32)
+    bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft2).cuda(), 0.3, 0, ocm, buffers=bf)
+    torch.cuda.synchronize()
+    assert csd.decode_ocm(ocm) == {(V - 1, 3): 1} and int(bf.status[csd.CSD_STATUS_DROPPED]) == 2
