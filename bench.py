@@ -301,6 +301,30 @@ def main() -> int:
     status = bf.status.cpu().numpy().view(np.uint32).tolist()
     elapsed_noupd, _, _ = timed_steps(0, args.steps, args.warmup)
 
+    # ---- for reference: two independent batches in flight (two streams, each with its own buffers and memory),
+    # so that one batch's finish kernel overlaps the other's streaming pass
+    def two_stream_rate(steps):
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        lanes = []
+        for st in (sa, sb):
+            with torch.cuda.stream(st):
+                lanes.append((st, csd.VerifyBuffers.allocate(cfg.B, cfg.k, cfg.V, dt), csd.new_ocm(cfg.capacity)))
+        torch.cuda.synchronize()
+        for i in range(4):
+            for st, b2, o2 in lanes:
+                with torch.cuda.stream(st):
+                    csd.csd_verify(ring_z[i % n_ring], ring_d[i % n_ring], cfg.tau, cfg.lam, o2, buffers=b2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            st, b2, o2 = lanes[i & 1]
+            with torch.cuda.stream(st):
+                csd.csd_verify(ring_z[i % n_ring], ring_d[i % n_ring], cfg.tau, cfg.lam, o2, buffers=b2)
+        torch.cuda.synchronize()
+        return rows * steps / (time.perf_counter() - t0)
+
+    rate_two_streams = two_stream_rate(args.steps)
+
     # ---- the dominant kernel: the streaming pass (csd_row_partials launches exactly the kernel and grid that
     # csd_verify launches first), same ring, events on the launch stream
     part = csd.csd_row_partials(ring_z[0])
@@ -347,6 +371,7 @@ def main() -> int:
             "positions_per_s_without_ocm_updates": rows * args.steps / elapsed_noupd,
             "ms_per_step_without_ocm_updates": elapsed_noupd / args.steps * 1e3,
             "ms_per_step_by_stream_events": step_ms_events,
+            "positions_per_s_two_batches_in_flight": rate_two_streams,
             "whole_path_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
             "whole_path_frac_of_hbm_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "accept_rate_last_step": accept_rate, "status_counters": status,
