@@ -107,8 +107,7 @@ def bench_sampled(args, cfg) -> int:
     from gen.workload import SampledWorkload
     from paper_2604_13634_amd import binding as csd
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from parity_util import to_device_logits
+    from gen.device import to_device_logits
 
     w = SampledWorkload(cfg)
     step_bytes = (cfg.rows + cfg.B * cfg.k) * cfg.V * cfg.itemsize
@@ -220,8 +219,7 @@ def main() -> int:
 
     from paper_2604_13634_amd import binding as csd
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from parity_util import to_device_logits
+    from gen.device import to_device_logits
 
     torch.cuda.set_device(0)
     if args.path == "sampled":

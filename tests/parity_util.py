@@ -8,33 +8,12 @@ float32 output cannot hold them to a relative bar).
 import numpy as np
 import torch
 
+from gen.device import to_device_logits  # noqa: F401  (re-exported for the tests)
 from oracle import csd_oracle as O
 from paper_2604_13634_amd import binding as csd
 
 RTOL = 1e-5
 ATOL = 1.1754944e-38          # FLT_MIN
-
-
-def to_device_logits(z: np.ndarray) -> torch.Tensor:
-    """Host logits (float32, or uint16 bf16 bit patterns) -> device tensor (float32 / bfloat16).
-
-    The library wants every row 16-byte aligned: when V * itemsize is not a multiple of 16 the rows
-    are laid out with a padded pitch (padding filled with a large value that must never be read) and
-    a [..., :V] view is returned."""
-    if z.dtype == np.float32:
-        t = torch.from_numpy(z)
-        per16, big = 4, 1e30
-    else:
-        assert z.dtype == np.uint16
-        t = torch.from_numpy(z.view(np.int16)).view(torch.bfloat16)
-        per16, big = 8, 1e30
-    V = z.shape[-1]
-    if V % per16 == 0:
-        return t.cuda()
-    pitch = (V + per16 - 1) // per16 * per16
-    padded = torch.full(z.shape[:-1] + (pitch,), big, dtype=t.dtype, device="cuda")
-    padded[..., :V] = t.cuda()
-    return padded[..., :V]
 
 
 def assert_close(gpu: np.ndarray, ref: np.ndarray, what: str):
