@@ -39,6 +39,16 @@ def test_full_size_step_with_prior(ci):
     assert rejected > 0
 
 
+@pytest.mark.parametrize("ci", [3, 4])
+def test_full_size_step_of_the_large_configurations(ci):
+    """Configurations 3 and 4 at full size (config 4 is the shape bench.py --path sampled times), one step."""
+    w = SampledWorkload(CONFIGS[ci])
+    prior = _prior(w, w.cfg.lam, min(512, w.cfg.n_pairs))
+    orc, ocm, rescued, counted, rejected = run_sampled_stream(w, range(1), 1.0, prior=prior, check_table_every=1,
+                                                              threads=16)
+    assert rejected > 0 and counted > 0
+
+
 def _one_step(zp, zq, draft, T, ua, ud, tau=0.3, lam=0, ocm_pairs=None, settle=True):
     if settle:
         ua, ud = settle_uniforms(zp, zq, draft, T, ua, ud, seed=1)
