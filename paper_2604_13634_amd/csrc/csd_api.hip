@@ -199,7 +199,8 @@ static SampledWorkspace sampled_layout(const StreamPlan &plan, int B, int k, int
     w.ticket_off = 0;
     w.partials_off = 256;
     w.rows_off = up(w.partials_off + (size_t)plan.rows * plan.partials_per_row * sizeof(RowPartial));
-    w.segsum_off = up(w.rows_off + (size_t)B * K1 * sizeof(DrawRow));
+    w.work_off = up(w.rows_off + (size_t)B * K1 * sizeof(DrawRow));
+    w.segsum_off = up(w.work_off + (size_t)B * K1 * sizeof(int32_t));
     w.zpd_off = up(w.segsum_off + (size_t)B * K1 * (size_t)nseg * sizeof(float));
     w.state_off = up(w.zpd_off + (size_t)B * k * sizeof(float));
     w.tstar_off = up(w.state_off + (size_t)B * k);
@@ -271,6 +272,8 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.partials_per_row = plan.partials_per_row;
     a.nseg = nseg;
     a.rows = (DrawRow *)(wsp + ws.rows_off);
+    a.work_count = (uint32_t *)(wsp + ws.ticket_off) + 1;
+    a.work_rows = (int32_t *)(wsp + ws.work_off);
     a.segsum = (float *)(wsp + ws.segsum_off);
     a.pos_zpd = (float *)(wsp + ws.zpd_off);
     a.pos_state = (uint8_t *)(wsp + ws.state_off);

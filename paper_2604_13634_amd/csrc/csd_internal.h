@@ -70,7 +70,7 @@ struct EpilogueArgs {
     uint8_t *pos_flags;
     uint64_t *rej_log;       // user log or workspace log; NULL when nothing needs it
     uint32_t *status;
-    uint32_t *batch_ticket;  // [1], zero when the finish kernel starts
+    uint32_t *batch_ticket;  // [2]: the ticket, and a spare counter; zero when the finish kernel starts
     int apply_updates;
 };
 
@@ -115,6 +115,8 @@ struct SampledArgs {
     int partials_per_row;
     int nseg;                  // segments per row
     DrawRow *rows;             // [B][k+1]
+    uint32_t *work_count;      // [1] number of rows that need a draw (the word after the batch ticket)
+    int32_t *work_rows;        // [B][k+1] their indices, in no particular order
     float *segsum;             // [B][k+1][nseg]
     float *pos_zpd;            // [B][k] target logit of the draft token
     uint8_t *pos_state;        // [B][k] bit0 acceptance test failed, bit1 draft id valid
@@ -134,7 +136,7 @@ struct SampledArgs {
 };
 
 struct SampledWorkspace {
-    size_t ticket_off, partials_off, rows_off, segsum_off, zpd_off, state_off, tstar_off, bonus_off, log_off, total;
+    size_t ticket_off, partials_off, rows_off, work_off, segsum_off, zpd_off, state_off, tstar_off, bonus_off, log_off, total;
 };
 int sampled_segments(int V, int dtype);
 hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);

@@ -13,9 +13,9 @@
 //      with the exponent scale log2(e)/T: maxima and normalisers at temperature T.        [HBM-bound]
 //   2. sampled_decide_kernel, one wave per sequence: combine the partials, p(x~), q(x~), alpha, the
 //      acceptance test; leaves for every "draw row" (a rejected position, or the bonus row) the constants
-//      that turn a logit into a probability.
-//   3. residual_segments_kernel over the draw rows only: streams the target row and the draft row side
-//      by side and leaves the residual mass of every segment of 256 chunks.               [HBM-bound]
+//      that turn a logit into a probability, and a list of the rows that need a draw.
+//   3. residual_segments_kernel, a fixed grid walking that list: streams the target row and the draft row
+//      side by side and leaves the residual mass of every segment of 256 chunks.          [HBM-bound]
 //   4. residual_locate_kernel, one wave per draw row: scans the segment masses in double, finds the
 //      segment that holds u*R, re-reads that one segment and walks to the token.
 //   5. sampled_finish_kernel, one wave per sequence: lookup, gate, accepted-prefix scan, emitted token,
@@ -29,8 +29,9 @@ namespace {
 
 constexpr int kSegLoads = 4;                          // 16-byte loads per lane and segment
 constexpr int kSegChunks = kWaveSize * kSegLoads;     // chunks per segment (one wave sweeps a segment)
-constexpr int kSegsPerWave = 4;                       // segments one wave of the segment kernel takes
+constexpr int kSegsPerWave = 2;                       // segments one wave takes per item: one round of loads
 constexpr int kSegBlockWaves = 4;
+constexpr int kSegGrid = 4096;                        // workgroups of the segment kernel (it walks a list)
 constexpr int kNone = 0x7fffffff;
 
 // probability of one logit from the row constants: 2^(z*scale - c) * f.  Separate roundings (no
@@ -88,10 +89,8 @@ __device__ __forceinline__ double wave_exclusive_scan_d(double v, int lane, doub
 
 // ---------------------------------------------------------------------------------------------------
 // Launch 2: acceptance test.  One wave per sequence; lane i < k owns draft position i, lane i <= k draw row i.
-__global__ __launch_bounds__(kApplyThreads) void sampled_decide_kernel(SampledArgs a) {
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (b >= a.B) return;
+// Returns, per lane, whether draw row `lane` of the sequence needs a draw.
+__device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int lane) {
     const int k = a.k, K1 = a.k + 1, P = a.partials_per_row;
     const bool is_pos = lane < k;
     const double scale = (double)a.scale;
@@ -160,58 +159,86 @@ __global__ __launch_bounds__(kApplyThreads) void sampled_decide_kernel(SampledAr
         r.u = a.u_draw[(int64_t)b * K1 + lane];
         r.pad = 0.f;
         a.rows[(int64_t)b * K1 + lane] = r;
+        return r.need != 0;
     }
+    return false;
+}
+
+__global__ __launch_bounds__(kApplyThreads) void sampled_decide_kernel(SampledArgs a) {
+    __shared__ unsigned int blk_count, blk_base;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    if (threadIdx.x == 0) blk_count = 0;
+    __syncthreads();
+    bool need = false;
+    if (b < a.B) need = decide_sequence(a, b, lane);      // wave-uniform: a wave takes a sequence or none
+    // the rows that need a draw go on a list (order immaterial), so that the second streaming pass launches
+    // work for them only: one LDS add per wave, one global add per workgroup
+    const uint64_t mask = __builtin_amdgcn_ballot_w64(need);
+    unsigned int off = 0;
+    if (lane == 0 && mask) off = atomicAdd(&blk_count, (unsigned int)__builtin_popcountll(mask));
+    off = __builtin_amdgcn_readfirstlane(off);
+    __syncthreads();
+    if (threadIdx.x == 0 && blk_count) blk_base = atomicAdd(a.work_count, blk_count);
+    __syncthreads();
+    if (need)
+        a.work_rows[blk_base + off + (unsigned int)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = b * (a.k + 1) + lane;
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 3: residual mass per segment, draw rows only.  grid.x = draw row, grid.y = groups of segments.
+// Launch 3: residual mass per segment, for the rows on the list only.  A fixed grid of workgroups walks the
+// items (row of the list, group of segments): no workgroup is launched for a row that needs nothing.
 template <int DT>
 __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
     using C = Chunk<DT>;
-    const int j = blockIdx.x;
-    const DrawRow r = a.rows[j];
-    if (!r.need) return;
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int K1 = a.k + 1;
-    const int b = j / K1, i = j - b * K1;
-    const bool use_q = i < a.k;
-    const int esz = (DT == CSD_DTYPE_F32) ? 4 : 2;
-    const char *prow = (const char *)a.target + (int64_t)j * a.target_stride * esz;
-    const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
-    const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
-    const int seg0 = (blockIdx.y * kSegBlockWaves + wave) * kSegsPerWave;
-    // two segments at a time: all their loads (2 x kSegLoads per tensor) are issued before any arithmetic
-    for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; s += 2) {
-        constexpr int N = 2 * kSegLoads;
-        u32x4 qp[N], qq[N];
-        if ((s + 2) * kSegChunks <= nfull) {                            // both segments are whole chunks of the row: no guards
+    const int groups = (a.nseg + kSegBlockWaves * kSegsPerWave - 1) / (kSegBlockWaves * kSegsPerWave);
+    const unsigned int items = *a.work_count * (unsigned int)groups;
+    for (unsigned int item = blockIdx.x; item < items; item += gridDim.x) {
+        const int j = a.work_rows[item / groups];
+        const int group = (int)(item % groups);
+        const DrawRow r = a.rows[j];
+        const int lane = threadIdx.x & (kWaveSize - 1);
+        const int wave = threadIdx.x >> 6;
+        const int K1 = a.k + 1;
+        const int b = j / K1, i = j - b * K1;
+        const bool use_q = i < a.k;
+        const int esz = (DT == CSD_DTYPE_F32) ? 4 : 2;
+        const char *prow = (const char *)a.target + (int64_t)j * a.target_stride * esz;
+        const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
+        const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
+        const int seg0 = (group * kSegBlockWaves + wave) * kSegsPerWave;
+        // two segments at a time: all their loads (2 x kSegLoads per tensor) are issued before any arithmetic
+        for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; s += 2) {
+            constexpr int N = 2 * kSegLoads;
+            u32x4 qp[N], qq[N];
+            if ((s + 2) * kSegChunks <= nfull) {                            // both segments are whole chunks of the row: no guards
+#pragma unroll
+                for (int u = 0; u < N; ++u) {
+                    const int ch = s * kSegChunks + u * kWaveSize + lane;   // segment s+1 follows segment s in memory
+                    qp[u] = __builtin_nontemporal_load((const u32x4 *)prow + ch);
+                    if (use_q) qq[u] = __builtin_nontemporal_load((const u32x4 *)qrow + ch);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < N; ++u) {
+                    const int ch = s * kSegChunks + u * kWaveSize + lane;
+                    qp[u] = stream_chunk_guarded<DT>(prow, ch, nfull, tail);
+                    if (use_q) qq[u] = stream_chunk_guarded<DT>(qrow, ch, nfull, tail);
+                }
+            }
+            float sum[2] = {0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < N; ++u) {
-                const int ch = s * kSegChunks + u * kWaveSize + lane;   // segment s+1 follows segment s in memory
-                qp[u] = __builtin_nontemporal_load((const u32x4 *)prow + ch);
-                if (use_q) qq[u] = __builtin_nontemporal_load((const u32x4 *)qrow + ch);
+                float w[C::E];
+                weights_of<DT>(qp[u], qq[u], use_q, a.scale, r, w);
+#pragma unroll
+                for (int e = 0; e < C::E; ++e) sum[u / kSegLoads] += w[e];
             }
-        } else {
-#pragma unroll
-            for (int u = 0; u < N; ++u) {
-                const int ch = s * kSegChunks + u * kWaveSize + lane;
-                qp[u] = stream_chunk_guarded<DT>(prow, ch, nfull, tail);
-                if (use_q) qq[u] = stream_chunk_guarded<DT>(qrow, ch, nfull, tail);
+            const float s0 = wave_allreduce_f(sum[0], AddF()), s1 = wave_allreduce_f(sum[1], AddF());
+            if (lane == 0) {
+                a.segsum[(int64_t)j * a.nseg + s] = s0;
+                if (s + 1 < a.nseg) a.segsum[(int64_t)j * a.nseg + s + 1] = s1;
             }
-        }
-        float sum[2] = {0.f, 0.f};
-#pragma unroll
-        for (int u = 0; u < N; ++u) {
-            float w[C::E];
-            weights_of<DT>(qp[u], qq[u], use_q, a.scale, r, w);
-#pragma unroll
-            for (int e = 0; e < C::E; ++e) sum[u / kSegLoads] += w[e];
-        }
-        const float s0 = wave_allreduce_f(sum[0], AddF()), s1 = wave_allreduce_f(sum[1], AddF());
-        if (lane == 0) {
-            a.segsum[(int64_t)j * a.nseg + s] = s0;
-            if (s + 1 < a.nseg) a.segsum[(int64_t)j * a.nseg + s + 1] = s1;
         }
     }
 }
@@ -412,7 +439,8 @@ hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int per_block = kSegBlockWaves * kSegsPerWave;
-    const dim3 seg_grid((unsigned)(a.B * K1), (unsigned)((a.nseg + per_block - 1) / per_block));
+    const int64_t max_items = (int64_t)a.B * K1 * ((a.nseg + per_block - 1) / per_block);
+    const dim3 seg_grid((unsigned)(max_items < kSegGrid ? max_items : kSegGrid));
     const dim3 row_grid((unsigned)(((int64_t)a.B * K1 + kFinishWaves - 1) / kFinishWaves));
     if (a.dtype == CSD_DTYPE_F32) {
         hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);

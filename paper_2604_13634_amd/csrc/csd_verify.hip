@@ -289,9 +289,10 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kerne
     const int split = blockIdx.x - row * nsplit;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    // the finish kernel's ticket starts every step at zero (kernel order makes this visible to it)
-    if (batch_ticket != nullptr && blockIdx.x == 0 && threadIdx.x == 0)
-        __hip_atomic_store(batch_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the later kernels' two counters (the batch ticket and, on the sampled path, the length of the list of
+    // rows to draw) start every step at zero (kernel order makes this visible to them)
+    if (batch_ticket != nullptr && blockIdx.x == 0 && threadIdx.x < 2)
+        __hip_atomic_store(&batch_ticket[threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     const char *rowp = (row < src.rows0) ? src.base0 + (int64_t)row * src.pitch0
                                          : src.base1 + (int64_t)(row - src.rows0) * src.pitch1;
