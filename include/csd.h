@@ -128,7 +128,7 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  *                         (nullable; with flags == 0 it can be replayed later through csd_ocm_update).
  *   status      [CSD_STATUS_WORDS] counters, incremented (nullable).
  * A step is two kernel launches: the streaming pass over the logits, then one wave per sequence for
- * the verification logic; the wave that completes the batch applies the updates (batches of more than
+ * the verification logic; the workgroup that completes the batch applies the updates (batches of more than
  * 8192 draft positions use a third launch for them).
  * Scratch
  *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; needs no
