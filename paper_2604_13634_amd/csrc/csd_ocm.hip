@@ -49,29 +49,41 @@ __global__ void ocm_merge_kernel(uint64_t *dst, uint64_t dst_capacity, const uin
 
 __global__ void zero_u64_kernel(unsigned long long *p) { *p = 0; }
 
-// compaction: one atomic per wave reserves room for the wave's occupied slots
+// compaction: a wave reads kExportLoads x 64 consecutive slots, reserves room for all their occupied ones with
+// ONE atomic (waves adding to the one counter are what this kernel waits for), then writes them out
+constexpr int kExportLoads = 16;
 __global__ void ocm_export_kernel(const uint64_t *__restrict__ ocm, uint64_t capacity, uint64_t *__restrict__ keys_out,
                                   uint32_t *__restrict__ counts_out, uint64_t max_entries, unsigned long long *n_out) {
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    const uint64_t first = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (kWaveSize - 1);
-    // whole waves iterate together (the bound is rounded up to the wave), so the ballot sees all 64 lanes
-    for (uint64_t base = first - lane; base < capacity; base += stride) {
-        const uint64_t i = base + lane;
-        const uint64_t s = (i < capacity) ? ocm[i] : CSD_OCM_EMPTY;
-        const bool used = slot_key(s) != CSD_OCM_EMPTY;
-        const uint64_t mask = __builtin_amdgcn_ballot_w64(used);
-        if (mask == 0) continue;
+    const uint64_t wave_id = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWaveSize;
+    const uint64_t waves = (uint64_t)gridDim.x * blockDim.x / kWaveSize;
+    const uint64_t span = (uint64_t)kExportLoads * kWaveSize;
+    for (uint64_t base = wave_id * span; base < capacity; base += waves * span) {     // wave-uniform bounds
+        uint64_t s[kExportLoads];
+        unsigned int total = 0;
+#pragma unroll
+        for (int u = 0; u < kExportLoads; ++u) {
+            const uint64_t i = base + (uint64_t)u * kWaveSize + lane;
+            s[u] = (i < capacity) ? ocm[i] : CSD_OCM_EMPTY;
+            total += (unsigned int)__builtin_popcountll(__builtin_amdgcn_ballot_w64(slot_key(s[u]) != CSD_OCM_EMPTY));
+        }
+        if (total == 0) continue;
         unsigned long long start = 0;
-        if (lane == 0) start = atomicAdd(n_out, (unsigned long long)__builtin_popcountll(mask));
+        if (lane == 0) start = atomicAdd(n_out, (unsigned long long)total);
         start = ((unsigned long long)__builtin_amdgcn_readfirstlane((int)(start >> 32)) << 32) |
                 (unsigned int)__builtin_amdgcn_readfirstlane((int)(start & 0xFFFFFFFFull));
-        if (used) {
-            const uint64_t pos = start + (uint64_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
-            if (pos < max_entries) {
-                keys_out[pos] = slot_key(s);
-                counts_out[pos] = slot_count(s);
+#pragma unroll
+        for (int u = 0; u < kExportLoads; ++u) {
+            const bool used = slot_key(s[u]) != CSD_OCM_EMPTY;
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(used);
+            if (used) {
+                const uint64_t pos = start + (uint64_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+                if (pos < max_entries) {
+                    keys_out[pos] = slot_key(s[u]);
+                    counts_out[pos] = slot_count(s[u]);
+                }
             }
+            start += (unsigned long long)__builtin_popcountll(mask);
         }
     }
 }
@@ -92,8 +104,9 @@ hipError_t launch_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *k
     hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, stream, (unsigned long long *)n_out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    uint64_t blocks = (capacity + 255) / 256;
+    uint64_t blocks = (capacity + 256 * kExportLoads - 1) / (256 * kExportLoads);   // a workgroup of 4 waves covers 4096 slots a round
     if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(ocm_export_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, ocm, capacity, keys_out, counts_out,
                        max_entries, (unsigned long long *)n_out);
     return hipGetLastError();
