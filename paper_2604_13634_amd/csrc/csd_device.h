@@ -116,17 +116,21 @@ constexpr int kApplyPerThread = kApplyBatch / kApplyThreads;
 
 struct ApplyLds {
     unsigned long long key[kApplySlots];
-    unsigned long long cnt[kApplySlots];          // 64-bit: kApplyBatch weights of up to 2^24-1 do not wrap
-    unsigned long long ckey[kApplyBatch];         // compacted distinct pairs ...
-    unsigned long long ccnt[kApplyBatch];         // ... and their summed weights
-    unsigned int ndistinct;
+    unsigned long long cnt[kApplySlots];          // 64-bit: sums of weights of up to 2^24-1 do not wrap
+    unsigned long long ckey[kApplySlots];         // compacted distinct pairs ...
+    unsigned long long ccnt[kApplySlots];         // ... and their summed weights
+    unsigned int nkeys;                           // distinct pairs in the table
+    unsigned int ndistinct;                       // length of the compacted list
 };
 
 __device__ __forceinline__ void lds_aggregate(ApplyLds &L, uint64_t key, uint32_t w) {
     uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) & (kApplySlots - 1);
     for (;;) {
         unsigned long long cur = L.key[i];
-        if (cur == CSD_OCM_EMPTY) cur = atomicCAS(&L.key[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
+        if (cur == CSD_OCM_EMPTY) {
+            cur = atomicCAS(&L.key[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
+            if (cur == CSD_OCM_EMPTY) atomicAdd(&L.nkeys, 1u);      // this thread put the pair in
+        }
         if (cur == CSD_OCM_EMPTY || cur == key) {
             atomicAdd(&L.cnt[i], (unsigned long long)w);
             return;
@@ -135,30 +139,21 @@ __device__ __forceinline__ void lds_aggregate(ApplyLds &L, uint64_t key, uint32_
     }
 }
 
-// Entries [base, min(base + kApplyBatch, n)) of a list; fetch(e, key, w) reads entry e.  Called by every
-// thread of the workgroup (it contains barriers).  Entries with an empty key or zero weight are skipped.
-template <typename Fetch>
-__device__ __forceinline__ void block_apply_batch(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L,
-                                                  Fetch fetch, uint64_t base, uint64_t n) {
-    const int tid = threadIdx.x;
-    uint64_t key[kApplyPerThread];
-    uint32_t w[kApplyPerThread];
-#pragma unroll
-    for (int j = 0; j < kApplyPerThread; ++j) {     // all global reads first: their latencies overlap
-        const uint64_t e = base + (uint64_t)(j * kApplyThreads + tid);
-        key[j] = CSD_OCM_EMPTY;
-        w[j] = 0;
-        if (e < n) fetch(e, key[j], w[j]);
-    }
-    for (int i = tid; i < kApplySlots; i += kApplyThreads) {
+// The three steps below are called by every thread of the workgroup (they contain barriers).
+__device__ __forceinline__ void block_apply_clear(ApplyLds &L) {
+    for (int i = threadIdx.x; i < kApplySlots; i += kApplyThreads) {
         L.key[i] = CSD_OCM_EMPTY;
         L.cnt[i] = 0;
     }
-    if (tid == 0) L.ndistinct = 0;
+    if (threadIdx.x == 0) {
+        L.nkeys = 0;
+        L.ndistinct = 0;
+    }
     __syncthreads();
-#pragma unroll
-    for (int j = 0; j < kApplyPerThread; ++j)
-        if (key[j] != CSD_OCM_EMPTY && w[j] != 0) lds_aggregate(L, key[j], w[j]);
+}
+// the table's pairs go to the memory, all of them side by side; the table is left empty
+__device__ __forceinline__ void block_apply_flush(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L) {
+    const int tid = threadIdx.x;
     __syncthreads();
     for (int i = tid; i < kApplySlots; i += kApplyThreads) {
         const unsigned long long sk = L.key[i];
@@ -175,7 +170,40 @@ __device__ __forceinline__ void block_apply_batch(uint64_t *ocm, uint64_t capaci
         const uint32_t ww = (sum > CSD_OCM_COUNT_MAX) ? CSD_OCM_COUNT_MAX : (uint32_t)sum;
         if (!ocm_add(ocm, capacity, L.ckey[i], ww) && status) atomicAdd(&status[CSD_STATUS_DROPPED], ww);
     }
-    __syncthreads();                                // the next batch reuses the LDS arrays
+    __syncthreads();
+    block_apply_clear(L);
+}
+
+// Batches first, first + stride, ... (of kApplyBatch entries each) of a list of n entries; fetch(e, key, w) reads
+// entry e.  Entries with an empty key or zero weight are skipped.  The LDS table keeps merging across batches
+// and is emptied into the memory only when the next batch might not fit, and at the end: a workgroup that
+// meets the same few pairs over and over sends each of them once.
+template <typename Fetch>
+__device__ __forceinline__ void block_apply_list(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L, Fetch fetch,
+                                                 uint64_t first, uint64_t stride, uint64_t n) {
+    const int tid = threadIdx.x;
+    block_apply_clear(L);
+    for (uint64_t base = first * kApplyBatch; base < n; base += stride * kApplyBatch) {
+        uint64_t key[kApplyPerThread];
+        uint32_t w[kApplyPerThread];
+#pragma unroll
+        for (int j = 0; j < kApplyPerThread; ++j) {     // all global reads first: their latencies overlap
+            const uint64_t e = base + (uint64_t)(j * kApplyThreads + tid);
+            key[j] = CSD_OCM_EMPTY;
+            w[j] = 0;
+            if (e < n) fetch(e, key[j], w[j]);
+        }
+        // Every thread must take the same branch (the flush has barriers): all read the count before anyone
+        // adds to it again.
+        const unsigned int have = L.nkeys;
+        __syncthreads();
+        if (have + kApplyBatch > (unsigned int)(kApplySlots - kApplySlots / 4)) block_apply_flush(ocm, capacity, status, L);
+#pragma unroll
+        for (int j = 0; j < kApplyPerThread; ++j)
+            if (key[j] != CSD_OCM_EMPTY && w[j] != 0) lds_aggregate(L, key[j], w[j]);
+        __syncthreads();                                // nkeys is read by every thread at the top of the next round
+    }
+    block_apply_flush(ocm, capacity, status, L);
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -370,7 +398,7 @@ __device__ __forceinline__ void apply_step_log(uint64_t *ocm, uint64_t capacity,
         key = xwg_load64(&rej_log[e]) & CSD_OCM_KEY_MASK;
         w = 1u;
     };
-    for (uint64_t base = 0; base < n; base += kApplyBatch) block_apply_batch(ocm, capacity, status, lds, fetch, base, n);
+    block_apply_list(ocm, capacity, status, lds, fetch, 0, 1, n);
 }
 
 __device__ __forceinline__ float load_logit(const void *logits, int dtype, int64_t elem) {

@@ -5,8 +5,10 @@
 namespace csd {
 namespace {
 
-// Each workgroup takes kApplyBatch entries: merges duplicate keys in LDS, then issues one compare-and-swap
-// chain per distinct key, so a skewed stream does not serialise on a handful of global slots.
+// A fixed grid of workgroups walks the list, kApplyBatch entries at a time per workgroup: duplicate keys are
+// merged in LDS across everything a workgroup sees, then one compare-and-swap chain per distinct key goes
+// to the table, so a skewed stream does not serialise on a handful of global slots.
+constexpr unsigned kUpdateGrid = 1024;
 __global__ __launch_bounds__(kApplyThreads) void ocm_update_kernel(uint64_t *ocm, uint64_t capacity,
                                                                    const uint64_t *__restrict__ keys,
                                                                    const uint32_t *__restrict__ weights, uint64_t n,
@@ -17,7 +19,7 @@ __global__ __launch_bounds__(kApplyThreads) void ocm_update_kernel(uint64_t *ocm
         w = weights ? weights[e] : 1u;
         if (w > CSD_OCM_COUNT_MAX) w = CSD_OCM_COUNT_MAX;
     };
-    block_apply_batch(ocm, capacity, status, lds, fetch, (uint64_t)blockIdx.x * kApplyBatch, n);
+    block_apply_list(ocm, capacity, status, lds, fetch, blockIdx.x, gridDim.x, n);
 }
 
 __global__ void ocm_reset_kernel(uint64_t *ocm, uint64_t capacity) {
@@ -115,7 +117,8 @@ hipError_t launch_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *k
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
                              uint32_t *status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const uint64_t blocks = (n + kApplyBatch - 1) / kApplyBatch;
+    uint64_t blocks = (n + kApplyBatch - 1) / kApplyBatch;
+    if (blocks > kUpdateGrid) blocks = kUpdateGrid;
     hipLaunchKernelGGL(ocm_update_kernel, dim3((unsigned)blocks), dim3(kApplyThreads), 0, stream, ocm, capacity, keys, weights, n,
                        status);
     return hipGetLastError();
