@@ -151,8 +151,9 @@ __device__ __forceinline__ void block_apply_clear(ApplyLds &L) {
     }
     __syncthreads();
 }
-// the table's pairs go to the memory, all of them side by side; the table is left empty
-__device__ __forceinline__ void block_apply_flush(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L) {
+// the table's pairs go to the memory, all of them side by side; the table is left empty when it is to be used again
+__device__ __forceinline__ void block_apply_flush(uint64_t *ocm, uint64_t capacity, uint32_t *status, ApplyLds &L,
+                                                  bool use_again) {
     const int tid = threadIdx.x;
     __syncthreads();
     for (int i = tid; i < kApplySlots; i += kApplyThreads) {
@@ -170,8 +171,10 @@ __device__ __forceinline__ void block_apply_flush(uint64_t *ocm, uint64_t capaci
         const uint32_t ww = (sum > CSD_OCM_COUNT_MAX) ? CSD_OCM_COUNT_MAX : (uint32_t)sum;
         if (!ocm_add(ocm, capacity, L.ckey[i], ww) && status) atomicAdd(&status[CSD_STATUS_DROPPED], ww);
     }
-    __syncthreads();
-    block_apply_clear(L);
+    if (use_again) {
+        __syncthreads();
+        block_apply_clear(L);
+    }
 }
 
 // Batches first, first + stride, ... (of kApplyBatch entries each) of a list of n entries; fetch(e, key, w) reads
@@ -197,13 +200,13 @@ __device__ __forceinline__ void block_apply_list(uint64_t *ocm, uint64_t capacit
         // adds to it again.
         const unsigned int have = L.nkeys;
         __syncthreads();
-        if (have + kApplyBatch > (unsigned int)(kApplySlots - kApplySlots / 4)) block_apply_flush(ocm, capacity, status, L);
+        if (have + kApplyBatch > (unsigned int)(kApplySlots - kApplySlots / 4)) block_apply_flush(ocm, capacity, status, L, true);
 #pragma unroll
         for (int j = 0; j < kApplyPerThread; ++j)
             if (key[j] != CSD_OCM_EMPTY && w[j] != 0) lds_aggregate(L, key[j], w[j]);
         __syncthreads();                                // nkeys is read by every thread at the top of the next round
     }
-    block_apply_flush(ocm, capacity, status, L);
+    block_apply_flush(ocm, capacity, status, L, false);
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
