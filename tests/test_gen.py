@@ -106,3 +106,29 @@ def test_zipf_head_is_heavy():
                     seen[int(draft[b, i])] = seen.get(int(draft[b, i]), 0) + 1
     top = max(seen.values())
     assert top > 0.3 * sum(seen.values())          # Zipf(1.5): rank 1 carries about 40 %
+
+
+def test_sampled_workload_is_seeded_and_shaped():
+    """Draft-model rows and uniforms of the sampling-temperature workload: deterministic by seed and step,
+    target rows identical to the greedy workload's, the drafted token on top of its draft row, the target's
+    top token planted below it, uniforms in [0, 1)."""
+    from gen.workload import SampledWorkload
+    for ci in (0, 1):
+        w = SampledWorkload(CONFIGS[ci], V=3001, B=3)
+        cfg = w.cfg
+        zp, zq, d, ua, ud = w.sampled_step(5)
+        zp2, zq2, d2, ua2, ud2 = SampledWorkload(CONFIGS[ci], V=3001, B=3).sampled_step(5)
+        for a, b in ((zp, zp2), (zq, zq2), (d, d2), (ua, ua2), (ud, ud2)):
+            assert np.array_equal(a, b)
+        z_greedy, d_greedy = Workload(CONFIGS[ci], V=3001, B=3).step(5)
+        assert np.array_equal(zp, z_greedy) and np.array_equal(d, d_greedy)
+        assert zp.shape == (cfg.B, cfg.k + 1, cfg.V) and zq.shape == (cfg.B, cfg.k, cfg.V)
+        assert ua.shape == (cfg.B, cfg.k) and ud.shape == (cfg.B, cfg.k + 1) and ua.dtype == np.float32
+        assert (ua >= 0).all() and (ua < 1).all() and (ud >= 0).all() and (ud < 1).all()
+        qf, pf = w.logits_as_f32(zq), w.logits_as_f32(zp)
+        assert np.array_equal(qf.argmax(-1), d)                          # the draft model is sure of what it drafted
+        top = pf[:, :cfg.k].argmax(-1)
+        differs = top != d
+        second = np.take_along_axis(qf, top[..., None], -1)[..., 0]
+        assert np.all(second[differs] > qf.max(-1)[differs] - 3.2)       # the target's choice sits within 3 below
+        assert not np.array_equal(w.sampled_step(6)[1], zq)
