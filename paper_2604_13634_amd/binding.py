@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 from dataclasses import dataclass
-from typing import Dict, Optional, Tuple
+from typing import Optional
 
 import torch
 
@@ -402,20 +402,3 @@ def csd_row_partials(logits: torch.Tensor, partials: Optional[torch.Tensor] = No
     if rc != CSD_OK:
         raise CsdError(rc, "csd_row_partials")
     return partials
-
-
-def decode_ocm(ocm: torch.Tensor) -> Dict[Tuple[int, int], int]:
-    """Copy a table to the host and unpack its slots into {(draft, target): count} (layout of csd.h)."""
-    import numpy as np
-    raw = ocm.detach().cpu().numpy().view(np.uint64)
-    key = raw & np.uint64(CSD_OCM_KEY_MASK)
-    used = key != np.uint64(CSD_OCM_EMPTY)
-    key = key[used]
-    cnt = (raw[used] >> np.uint64(CSD_OCM_KEY_BITS)).astype(np.int64)
-    d = (key >> np.uint64(20)).astype(np.int64)
-    t = (key & np.uint64((1 << 20) - 1)).astype(np.int64)
-    out: Dict[Tuple[int, int], int] = {}
-    for a, b, c in zip(d.tolist(), t.tolist(), cnt.tolist()):
-        assert (a, b) not in out, "a key occupies two slots"
-        out[(a, b)] = c
-    return out

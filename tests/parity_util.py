@@ -47,8 +47,24 @@ def compare_step(res: O.StepResult, bf: csd.VerifyBuffers, where: str = ""):
         assert got == res.log[b], "%s rej_log of sequence %d: %r != %r" % (where, b, got, res.log[b])
 
 
+def decode_ocm(ocm: torch.Tensor):
+    """Copy a table to the host and unpack its slots into {(draft, target): count} (slot layout of csd.h)."""
+    raw = ocm.detach().cpu().numpy().view(np.uint64)
+    key = raw & np.uint64(csd.CSD_OCM_KEY_MASK)
+    used = key != np.uint64(csd.CSD_OCM_EMPTY)
+    key = key[used]
+    cnt = (raw[used] >> np.uint64(csd.CSD_OCM_KEY_BITS)).astype(np.int64)
+    d = (key >> np.uint64(20)).astype(np.int64)
+    t = (key & np.uint64((1 << 20) - 1)).astype(np.int64)
+    out = {}
+    for a, b, c in zip(d.tolist(), t.tolist(), cnt.tolist()):
+        assert (a, b) not in out, "a key occupies two slots"
+        out[(a, b)] = c
+    return out
+
+
 def compare_table(ocm: torch.Tensor, orc: O.CSDOracle, where: str = ""):
-    got = csd.decode_ocm(ocm)
+    got = decode_ocm(ocm)
     assert got == orc.T, "%s: memory differs (gpu %d keys, oracle %d keys)" % (where, len(got), len(orc.T))
 
 

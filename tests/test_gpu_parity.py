@@ -8,7 +8,7 @@ import torch
 from gen import CONFIGS, Workload, f32_to_bf16_bits
 from oracle import csd_oracle as O
 from paper_2604_13634_amd import binding as csd
-from parity_util import compare_step, compare_table, run_stream, to_device_logits
+from parity_util import compare_step, compare_table, decode_ocm, run_stream, to_device_logits
 
 pytestmark = pytest.mark.gpu
 
@@ -310,14 +310,14 @@ def test_ocm_hot_key_contention_and_saturation():
     keys = torch.from_numpy((d.astype(np.int64) << 20) | t.astype(np.int64)).cuda()
     ocm = csd.new_ocm(64)
     csd.csd_ocm_update(ocm, keys)
-    got = csd.decode_ocm(ocm)
+    got = decode_ocm(ocm)
     assert got == {(i, i + 10): int((d == i).sum()) for i in range(4)}
     big = torch.full((40,), 2 ** 31 - 1, dtype=torch.int32, device="cuda")
     csd.csd_ocm_update(ocm, keys[:40], big)
-    got = csd.decode_ocm(ocm)
+    got = decode_ocm(ocm)
     assert all(got[(int(a), int(a) + 10)] == csd.CSD_OCM_COUNT_MAX for a in set(d[:40].tolist()))
     csd.csd_ocm_update(ocm, keys[:40])
-    assert csd.decode_ocm(ocm) == got
+    assert decode_ocm(ocm) == got
 
 
 def test_ocm_full_table_drops_are_reported():
@@ -336,7 +336,7 @@ def test_ocm_full_table_drops_are_reported():
     csd.csd_ocm_update(ocm, keys[:1], None, status)
     assert csd.csd_ocm_lookup(ocm, keys).cpu().tolist() == [4, 0]
     csd.csd_ocm_reset(ocm)
-    assert csd.decode_ocm(ocm) == {}
+    assert decode_ocm(ocm) == {}
 
 
 def test_ocm_merge_export_rehash_roundtrip():
@@ -391,7 +391,7 @@ def test_ocm_merge_export_rehash_roundtrip():
                        torch.tensor([csd.CSD_OCM_COUNT_MAX - 3], dtype=torch.int32, device="cuda"))
     sat2 = sat.clone()
     csd.csd_ocm_merge(sat, sat2)
-    assert csd.decode_ocm(sat) == {(5, 6): csd.CSD_OCM_COUNT_MAX}
+    assert decode_ocm(sat) == {(5, 6): csd.CSD_OCM_COUNT_MAX}
 
 
 def test_two_streams_share_one_memory():
@@ -630,9 +630,9 @@ def test_largest_vocabulary_and_smallest_table(dtype):
     res = orc.verify_step(z, draft, tau=np.float32(0.3), lam=0)
     compare_step(res, bf, "V=2^20")
     assert bf.argmax.cpu().tolist() == [[3, V - 1], [V - 2, 12345]]
-    assert csd.decode_ocm(ocm) == {(V - 1, 3): 1} == orc.T          # the pair of sequence 0; sequence 1 matched
+    assert decode_ocm(ocm) == {(V - 1, 3): 1} == orc.T          # the pair of sequence 0; sequence 1 matched
     # a second pair finds the single slot taken: dropped, and said so
     draft2 = np.array([[5], [7]], dtype=np.int32)
     bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft2).cuda(), 0.3, 0, ocm, buffers=bf)
     torch.cuda.synchronize()
-    assert csd.decode_ocm(ocm) == {(V - 1, 3): 1} and int(bf.status[csd.CSD_STATUS_DROPPED]) == 2
+    assert decode_ocm(ocm) == {(V - 1, 3): 1} and int(bf.status[csd.CSD_STATUS_DROPPED]) == 2

@@ -8,7 +8,8 @@ from gen.workload import SampledWorkload
 from oracle import csd_oracle as O
 from oracle import csd_oracle_sampled as OS
 from paper_2604_13634_amd import binding as csd
-from parity_util import (compare_sampled_step, compare_table, run_sampled_stream, settle_uniforms, to_device_logits)
+from parity_util import (compare_sampled_step, compare_table, decode_ocm, run_sampled_stream, settle_uniforms,
+                         to_device_logits)
 
 pytestmark = pytest.mark.gpu
 
@@ -156,7 +157,7 @@ def test_small_temperature_agrees_with_the_greedy_entry_point():
         assert torch.equal(g.pos_flags, s.pos_flags)
         rescued += int(s.status[csd.CSD_STATUS_RESCUED])
     assert rescued > 5
-    assert csd.decode_ocm(ocm_g) == csd.decode_ocm(ocm_s) and len(csd.decode_ocm(ocm_g)) > 10
+    assert decode_ocm(ocm_g) == decode_ocm(ocm_s) and len(decode_ocm(ocm_g)) > 10
 
 
 @pytest.mark.parametrize("B,k,V", [(2200, 4, 520), (3, 31, 1500), (2, 63, 900), (300, 7, 1030)])
