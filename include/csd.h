@@ -143,6 +143,26 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
                void *stream);
 
 /*
+ * csd_verify_static - csd_verify for callers that cannot hand over or allocate scratch memory: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results,
+ * kernels and return codes as csd_verify, without `workspace`: the scratch is a CSD_STATIC_SCRATCH_BYTES array
+ * inside the library's code object, one copy per GPU, held by every GPU the library runs on until the process
+ * ends.  The call allocates and frees nothing; its first use on a device looks the array's device address up
+ * once (with that device current - make that first call outside a capture).  `stream` must belong to the
+ * current device.
+ *   Shapes whose csd_verify_workspace_bytes() exceeds CSD_STATIC_SCRATCH_BYTES return CSD_ENOSPACE (nothing
+ *   is enqueued); all five workloads of the benchmark need less than 0.4 MiB.
+ *   Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads)
+ *   race and give undefined results - order them, or use csd_verify with separate workspaces.  The array keeps
+ *   the last call's contents; nothing in it has to be cleared between calls.
+ */
+#define CSD_STATIC_SCRATCH_BYTES (4u << 20)
+int csd_verify_static(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+                      uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+                      int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+                      uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *stream);
+
+/*
  * csd_verify_sampled - one verification step at a sampling temperature T > 0 (Algorithm 1 as printed:
  * acceptance test of Eq. 2, correction token from the normalised residual, memory, gate of Eq. 3).  The
  * uniform random numbers the algorithm draws are inputs, so that a run can be reproduced and checked.

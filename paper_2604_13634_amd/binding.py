@@ -23,6 +23,7 @@ CSD_APPLY_UPDATES = 1
 CSD_MAX_K = 63
 CSD_MAX_V = 1 << 20
 CSD_MAX_SHARDS = 8
+CSD_STATIC_SCRATCH_BYTES = 4 << 20
 CSD_OCM_KEY_BITS = 40
 CSD_OCM_KEY_MASK = (1 << 40) - 1
 CSD_OCM_EMPTY = (1 << 40) - 1
@@ -57,6 +58,9 @@ def load_library() -> ctypes.CDLL:
     lib.csd_verify.restype = i32
     lib.csd_verify.argtypes = [vp, i32, i64, vp, i32, i32, i32, f32, u32, vp, u64, u32,
                                vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.csd_verify_static.restype = i32
+    lib.csd_verify_static.argtypes = [vp, i32, i64, vp, i32, i32, i32, f32, u32, vp, u64, u32,
+                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.csd_verify_sampled_workspace_bytes.restype = sz
     lib.csd_verify_sampled_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.csd_verify_sampled.restype = i32
@@ -162,7 +166,8 @@ def _current_stream_handle() -> int:
 
 def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
                ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
-               buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True) -> VerifyBuffers:
+               buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True,
+               static_scratch: bool = False) -> VerifyBuffers:
     """Enqueue one verification step.  logits: [B][k+1][V] (float32 or bfloat16), draft: [B][k] int32.
 
     Returns the VerifyBuffers holding the outputs (valid once the stream has run the call).
@@ -199,12 +204,26 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
         st = _current_stream_handle()
     else:
         st = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    if static_scratch:
+        rc = load_library().csd_verify_static(
+            logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
+            None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags, *outs[:10], st or None)
+        if rc != CSD_OK:
+            raise CsdError(rc, "csd_verify_static")
+        return bf
     rc = load_library().csd_verify(
         logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
         None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags, *outs, st or None)
     if rc != CSD_OK:
         raise CsdError(rc, "csd_verify")
     return bf
+
+
+def csd_verify_static(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
+                      ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+                      buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True) -> VerifyBuffers:
+    """csd_verify on the library's own per-GPU scratch array (the workspace of `buffers` is not used)."""
+    return csd_verify(logits, draft, tau, lam, ocm, flags, buffers, stream, diagnostics, static_scratch=True)
 
 
 def _rows_stride(t: torch.Tensor, what: str) -> int:

@@ -1,5 +1,6 @@
 // C ABI of the CSD verification library: argument validation and kernel sequencing.
 // Nothing here allocates, frees or synchronises; every entry point only enqueues on the caller's stream.
+#include <atomic>
 #include <cstring>
 
 #include "csd_internal.h"
@@ -30,19 +31,33 @@ bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 using namespace csd;
 
-extern "C" {
+// Scratch of csd_verify_static: one copy per GPU, loaded with the code object and held until the process ends.
+// The name below is a host-side stand-in, not a device address: host code only ever uses the pointer that
+// hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[CSD_STATIC_SCRATCH_BYTES];
 
-size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype) {
-    if (!shape_ok(B, k, V, dtype)) return 0;
-    const StreamPlan p = make_stream_plan(B * (k + 1), V, dtype);
-    return make_workspace_layout(p, B, k).total;
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; looked up once per device (no allocation), nullptr on error.
+void *static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p != nullptr) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
 }
+}  // namespace
 
-int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
-               uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
-               int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
-               uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
-               void *stream) {
+// One greedy verification step on the given scratch memory: validation, then the two (or three) launches.
+static int verify_step(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+                       uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+                       int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+                       uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+                       void *stream) {
     if (!shape_ok(B, k, V, dtype)) return CSD_EINVAL;
     if (is_nan_bits(tau)) return CSD_EINVAL;
     if (flags & ~CSD_APPLY_UPDATES) return CSD_EINVAL;
@@ -107,6 +122,38 @@ int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t 
         if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
     }
     return CSD_OK;
+}
+
+
+extern "C" {
+
+size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype) {
+    if (!shape_ok(B, k, V, dtype)) return 0;
+    const StreamPlan p = make_stream_plan(B * (k + 1), V, dtype);
+    return make_workspace_layout(p, B, k).total;
+}
+
+int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+               uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+               int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+               uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *workspace, size_t workspace_bytes,
+               void *stream) {
+    return verify_step(logits, dtype, row_stride, draft, B, k, V, tau, lambda, ocm, capacity, flags, accept_len, next_token,
+                       argmax, row_max, row_sumexp, ratio, p_draft, pos_flags, rej_log, status, workspace, workspace_bytes,
+                       stream);
+}
+
+int csd_verify_static(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,
+                      uint32_t lambda, uint64_t *ocm, uint64_t capacity, uint32_t flags, int32_t *accept_len,
+                      int32_t *next_token, int32_t *argmax, float *row_max, float *row_sumexp, float *ratio, float *p_draft,
+                      uint8_t *pos_flags, uint64_t *rej_log, uint32_t *status, void *stream) {
+    if (!shape_ok(B, k, V, dtype)) return CSD_EINVAL;
+    if (csd_verify_workspace_bytes(B, k, V, dtype) > (size_t)CSD_STATIC_SCRATCH_BYTES) return CSD_ENOSPACE;
+    void *ws = static_scratch_of_current_device();
+    if (ws == nullptr) return CSD_EHIP;
+    return verify_step(logits, dtype, row_stride, draft, B, k, V, tau, lambda, ocm, capacity, flags, accept_len, next_token,
+                       argmax, row_max, row_sumexp, ratio, p_draft, pos_flags, rej_log, status, ws, CSD_STATIC_SCRATCH_BYTES,
+                       stream);
 }
 
 size_t csd_verify_shards_workspace_bytes(int B, int k) {
