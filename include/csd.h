@@ -75,7 +75,9 @@ extern "C" {
 #define CSD_STATUS_RESCUED 2   /* positions kept by the memory + gate although draft != t*       */
 #define CSD_STATUS_COUNTED 3   /* divergences handed to UpdateMemory                             */
 #define CSD_STATUS_ACCEPTED 4   /* draft tokens kept, summed over sequences (acceptance rate = this / (B*k) per call) */
-#define CSD_STATUS_WORDS 8     /* words 5..7 are reserved and left untouched */
+#define CSD_STATUS_STALLED 5   /* waits inside a step that ran out (a GPU starved by other work for seconds): the
+                                  sequences concerned report accept_len 0 and next_token -1, their updates are skipped */
+#define CSD_STATUS_WORDS 8     /* words 6..7 are reserved and left untouched */
 
 /* pos_flags bits, per draft position; 0 for positions after the stop */
 #define CSD_POS_MATCH 1u     /* draft == t*                                        */

@@ -29,6 +29,7 @@ CSD_OCM_KEY_MASK = (1 << 40) - 1
 CSD_OCM_EMPTY = (1 << 40) - 1
 CSD_OCM_COUNT_MAX = (1 << 24) - 1
 CSD_STATUS_DROPPED, CSD_STATUS_BAD_DRAFT, CSD_STATUS_RESCUED, CSD_STATUS_COUNTED, CSD_STATUS_ACCEPTED = 0, 1, 2, 3, 4
+CSD_STATUS_STALLED = 5
 CSD_STATUS_WORDS = 8
 CSD_POS_MATCH, CSD_POS_FREQ, CSD_POS_SAFE, CSD_POS_ACCEPTED, CSD_POS_COUNTED = 1, 2, 4, 8, 16
 

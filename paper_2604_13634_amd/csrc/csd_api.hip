@@ -1,6 +1,7 @@
 // C ABI of the CSD verification library: argument validation and kernel sequencing.
 // Nothing here allocates, frees or synchronises; every entry point only enqueues on the caller's stream.
 #include <atomic>
+#include <chrono>
 #include <cstring>
 
 #include "csd_internal.h"
@@ -37,6 +38,18 @@ using namespace csd;
 static __device__ __align__(256) unsigned char scratch[CSD_STATIC_SCRATCH_BYTES];
 
 namespace {
+// A number that differs from call to call (and, by its starting point, from process to process): the records
+// that the waves of a step hand to each other are tagged with it, so what an earlier call left in a workspace
+// never passes for this call's.
+uint64_t next_call_number() {
+    static std::atomic<uint64_t> counter{[] {
+        uint64_t x = (uint64_t)std::chrono::steady_clock::now().time_since_epoch().count();
+        x ^= (uint64_t)(uintptr_t)&x * 0x9E3779B97F4A7C15ull;
+        return x | 1ull;
+    }()};
+    return counter.fetch_add(0x9E3779B97F4A7C15ull, std::memory_order_relaxed);
+}
+
 constexpr int kMaxDevices = 64;
 std::atomic<void *> g_scratch_ptr[kMaxDevices];
 
@@ -78,7 +91,6 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     if (workspace_bytes < ws.total) return CSD_ENOSPACE;
 
     hipStream_t st = (hipStream_t)stream;
-    RowPartial *partials = (RowPartial *)((char *)workspace + ws.partials_off);
     const bool apply = (flags & CSD_APPLY_UPDATES) && ocm != nullptr && k > 0;
     uint64_t *log = rej_log ? rej_log : (apply ? (uint64_t *)((char *)workspace + ws.log_off) : nullptr);
 
@@ -96,7 +108,7 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     a.capacity = capacity;
     a.sharded = 0;
     a.n_shards = 1;
-    a.shard_partials[0] = partials;
+    a.shard_partials[0] = nullptr;                        // the records of the single-launch step take their place
     a.shard_per_row[0] = plan.partials_per_row;
     a.shard_base[0] = 0;
     a.draft_logit = nullptr;
@@ -110,15 +122,22 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     a.pos_flags = pos_flags;
     a.rej_log = log;
     a.status = status;
-    a.batch_ticket = (uint32_t *)((char *)workspace + ws.ticket_off);
-    // The step's increments are applied inside the finish kernel by the wave that completes the batch;
-    // very large batches hand them to the bulk update kernel instead (one more launch, many workgroups).
-    const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
-    a.apply_updates = update_in_finish ? 1 : 0;
+    a.batch_ticket = nullptr;
+    // One launch does the whole step.  The step's increments are applied inside it by the sequence waves
+    // themselves while their workgroups are few enough to wait for each other; larger batches hand the log to
+    // the bulk update kernel (one more launch, many workgroups).
+    const int n_seq_wgs = (B + kStepSeqWaves - 1) / kStepSeqWaves;
+    const bool update_here = apply && n_seq_wgs <= kMaxBarrierWorkgroups;
+    a.apply_updates = update_here ? 1 : 0;
+    a.update_here = update_here ? 1 : 0;
+    if (update_here && !rej_log) a.rej_log = nullptr;      // nobody reads a log then
+    a.records = (StepRecord *)((char *)workspace + ws.partials_off);
+    a.ctrl = (StepControl *)((char *)workspace + ws.ticket_off);
+    a.nonce = next_call_number();
+    a.n_stream_wgs = plan.rows * plan.nsplit;
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, plan.rows, nullptr, 0, CSD_LOG2E_F32};
-    if (launch_row_partials(src, dtype, V, plan, partials, a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
-    if (launch_finish(a, st) != hipSuccess) return CSD_EHIP;
-    if (apply && !update_in_finish) {
+    if (launch_verify_step(src, dtype, V, plan, a, st) != hipSuccess) return CSD_EHIP;
+    if (apply && !update_here) {
         if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
     }
     return CSD_OK;

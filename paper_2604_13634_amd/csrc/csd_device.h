@@ -104,6 +104,82 @@ __device__ inline bool ocm_add(uint64_t *ocm, uint64_t capacity, uint64_t key, u
     return false;
 }
 
+// Where a lookup ended: at the pair's slot (found, with its count), at the empty slot that ends its probe
+// chain (the slot an insert would try first), or nowhere (every slot holds another pair).  Slots are never
+// freed or moved, so a found slot stays the pair's slot for the life of the table.
+struct OcmProbe {
+    uint64_t slot;
+    uint32_t count;
+    bool found;
+    bool full;
+};
+__device__ inline OcmProbe ocm_probe(const uint64_t *ocm, uint64_t capacity, uint64_t key) {
+    OcmProbe r;
+    r.slot = home_slot(key, capacity);
+    r.count = 0;
+    r.found = false;
+    r.full = false;
+    for (uint64_t probe = 0; probe < capacity; ++probe) {
+        const uint64_t s = __hip_atomic_load(&ocm[r.slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t sk = slot_key(s);
+        if (sk == key) {
+            r.found = true;
+            r.count = slot_count(s);
+            return r;
+        }
+        if (sk == CSD_OCM_EMPTY) return r;
+        r.slot = (r.slot + 1) & (capacity - 1);
+    }
+    r.full = true;
+    return r;
+}
+
+// First half of an insert, usable before the step's other lookups have finished: claim the empty slot the probe
+// ended at for `key`, with count ZERO.  A pair that is absent and a pair that is present with count zero read
+// the same in every lookup, so this changes no decision of the step; the count is added later.  The result
+// (`won`, and what the slot held otherwise) is first looked at in ocm_add_one_after_claim, so the
+// compare-and-swap can stay in flight while the caller does other things.
+struct OcmClaim {
+    uint64_t seen;       // content of the slot when the claim lost
+    bool tried, won;
+};
+__device__ __forceinline__ OcmClaim ocm_claim_after_probe(uint64_t *ocm, uint64_t key, const OcmProbe &pr) {
+    OcmClaim c;
+    c.seen = CSD_OCM_EMPTY;
+    c.tried = !pr.found && !pr.full;
+    c.won = false;
+    if (c.tried)
+        c.won = __hip_atomic_compare_exchange_strong(&ocm[pr.slot], &c.seen, key, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+    return c;
+}
+
+constexpr uint32_t kHintHeadroom = 1u << 20;   // increments by others allowed for between a probe and the add that uses it
+
+// Second half: the pair sits at pr.slot (found by the probe, or claimed there since - by this lane or, a moment
+// ago, by another lane of the step) and takes one atomic add; anything else goes the general way.
+__device__ inline bool ocm_add_one_after_claim(uint64_t *ocm, uint64_t capacity, uint64_t key, const OcmProbe &pr,
+                                               const OcmClaim &c) {
+    const bool here = (pr.found && pr.count < CSD_OCM_COUNT_MAX - kHintHeadroom) ||
+                      (c.tried && (c.won || (slot_key(c.seen) == key && slot_count(c.seen) < CSD_OCM_COUNT_MAX - kHintHeadroom)));
+    if (here) {
+        __hip_atomic_fetch_add(&ocm[pr.slot], 1ull << CSD_OCM_KEY_BITS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    }
+    return ocm_add(ocm, capacity, key, 1u);
+}
+
+// A workgroup barrier that waits for LDS traffic only: values handed round through LDS are complete, stores and
+// atomics to global memory may still be in flight (a plain __syncthreads waits for every one of them to be
+// acknowledged, a memory round trip).  The empty asm statements keep the compiler from moving memory
+// operations across it.
+__device__ __forceinline__ void barrier_lds_only() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0); vmcnt and expcnt left alone
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // ---- applying a list of (key, weight) entries to the table, one workgroup of kApplyThreads threads.
 // Entries are merged in an LDS hash table first, kApplyBatch at a time, so a skewed list costs one
 // compare-and-swap chain per DISTINCT pair; the distinct pairs are then compacted so that all of them
@@ -274,7 +350,10 @@ __device__ __forceinline__ uint64_t xwg_load64(const uint64_t *p) {
 // (s_waitcnt vmcnt(0): on gfx9 the counter covers stores, and a write-through store is acknowledged once
 // it is visible at agent scope) - a workgroup barrier alone does not wait for them.  The second barrier
 // hands the verdict round; the reads of the log depend on it, so they cannot be issued early.
+// The workgroup-scope fences cost no cache maintenance; they keep the compiler from moving the log's stores
+// below the ticket or the log's loads above the verdict.
 __device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t total, int *verdict) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0); expcnt and lgkmcnt left alone
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -282,6 +361,7 @@ __device__ __forceinline__ bool take_last_ticket(uint32_t *ticket, uint32_t tota
         *verdict = (old == total - 1);
     }
     __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     return *verdict != 0;
 }
 
@@ -342,12 +422,21 @@ __device__ __forceinline__ void partials_sum_merge(int G, double &S) {
     for (int x = 1; x < G; x <<= 1) S += xchg_d(S, x);
 }
 // A row whose partials fit NB registers per lane (the usual case) is read ONCE, all loads in flight together.
+// the arithmetic of the combine on partials already in registers (unused entries = empty_partial())
+template <int NB>
+__device__ __forceinline__ void combine_partials_in_registers(const RowPartial (&q)[NB], int G, double scale, float &gm, int &t,
+                                                              double &S);
 template <int NB>
 __device__ __forceinline__ void combine_row_partials_once(const RowPartial *pp, int P, int G, int gs, double scale, float &gm,
                                                           int &t, double &S) {
     RowPartial q[NB];
 #pragma unroll
     for (int u = 0; u < NB; ++u) q[u] = (gs + u * G < P) ? pp[gs + u * G] : empty_partial();
+    combine_partials_in_registers<NB>(q, G, scale, gm, t, S);
+}
+template <int NB>
+__device__ __forceinline__ void combine_partials_in_registers(const RowPartial (&q)[NB], int G, double scale, float &gm, int &t,
+                                                              double &S) {
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
         if (q[u].m > gm || (q[u].m == gm && q[u].idx < t)) t = q[u].idx;

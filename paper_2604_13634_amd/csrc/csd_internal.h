@@ -32,10 +32,31 @@ struct StreamPlan {
 
 StreamPlan make_stream_plan(int rows, int V, int dtype);
 
-// csd_verify workspace: [batch ticket | partials | rejection log].  Nothing in it outlives a call.
+// What a streaming wave of the single-launch step hands to the sequence waves of the same launch: its row
+// partial (w0 = m | cref << 32, w1 = s | idx << 32) and a check word, a 64-bit hash of the two data words, of a
+// per-call number and of the record's index.  A reader takes a record as written once the check holds (a torn
+// read fails it); arbitrary memory passes with probability 2^-64, so the workspace needs no initialisation.
+// Readers zero the check word after use: a replay of the same call (a captured graph carries the same per-call
+// number) then starts from records that do not pass.
+struct StepRecord {
+    uint64_t w0, w1, check, pad;
+};
+static_assert(sizeof(StepRecord) == 32, "records are 32 bytes");
+
+// Head of the csd_verify workspace.  `arrivals` is the counter behind the barrier of the sequence workgroups;
+// it is zero between calls (the last workgroup through resets it).  `magic` says that this has been set up:
+// the first workgroup of a launch that finds another value there zeroes the counter and writes the magic.
+struct StepControl {
+    uint64_t magic;
+    uint32_t arrivals;
+    uint32_t pad;
+};
+constexpr uint64_t kStepMagic = 0x3153444e56445343ull;
+
+// csd_verify workspace: [control | records | rejection log].  Nothing but the control head outlives a call.
 struct WorkspaceLayout {
-    size_t ticket_off;
-    size_t partials_off, partials_bytes;
+    size_t ticket_off;                       // the control head (the ticket of the two-launch forms lives here too)
+    size_t partials_off, partials_bytes;     // StepRecord per streaming wave
     size_t log_off, log_bytes;
     size_t total;
 };
@@ -72,6 +93,12 @@ struct EpilogueArgs {
     uint32_t *status;
     uint32_t *batch_ticket;  // [2]: the ticket, and a spare counter; zero when the finish kernel starts
     int apply_updates;
+    // single-launch step only
+    StepRecord *records;     // [rows][partials_per_row]
+    StepControl *ctrl;
+    uint64_t nonce;          // per-call number behind the records' tags
+    int n_stream_wgs;        // workgroups [0, n_stream_wgs) stream rows, the rest take sequences
+    int update_here;         // 1: the sequence waves apply their own increments after a barrier among their workgroups
 };
 
 // Where the rows of a streaming launch live: rows [0, rows0) in tensor 0, the others in tensor 1
@@ -145,6 +172,10 @@ hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
                                uint32_t *batch_ticket, hipStream_t stream);
 hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
+hipError_t launch_verify_step(const StreamSource &src, int dtype, int V, const StreamPlan &plan, const EpilogueArgs &a,
+                              hipStream_t stream);
+constexpr int kStepSeqWaves = kStreamWaves;      // sequences per workgroup of the single-launch step's second role
+constexpr int kMaxBarrierWorkgroups = 64;        // sequence workgroups that may wait for each other inside a launch
 hipError_t launch_zero_ticket(uint32_t *ticket, hipStream_t stream);
 hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
                                      const int32_t *draft, float *draft_logit, hipStream_t stream);

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
         for (int s = s0; s < s0 + per && s < a.nseg; ++s) {
             const double v = (double)seg[s];
             if (v > 0.0) lastpos = s;
-            if (found == kNone && acc + v > target) {
+            if (found == kNone && v > 0.0 && acc + v > target) {    // a segment without mass is never chosen
                 found = s;
                 base = acc;
             }
@@ -288,7 +288,9 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
             found = kNone - 1;                             // nobody owns `base`: walk the segment from its start with rem = +inf
         }
         const int owner = sstar / per;
-        double rem = (found == kNone - 1) ? INFINITY : target - from_lane_d(base, owner);
+        // `base` comes from the owner's serial adds, `target` was compared against a tree scan: clamp what is
+        // left at zero so that the walk below starts inside the segment
+        double rem = (found == kNone - 1) ? INFINITY : fmax(target - from_lane_d(base, owner), 0.0);
         // ---- inside the segment, in token order: load u, then lane, then element
         const int esz = (DT == CSD_DTYPE_F32) ? 4 : 2;
         const bool use_q = i < a.k;
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
             last_tok = my_last > last_tok ? my_last : last_tok;
             double tot;
             const double excl = wave_exclusive_scan_d(lsum, lane, tot);
-            const uint64_t hit = __builtin_amdgcn_ballot_w64(excl + lsum > rem);
+            const uint64_t hit = __builtin_amdgcn_ballot_w64(lsum > 0.0 && excl + lsum > rem);   // only lanes holding mass
             if (hit) {
                 const int L = (int)__builtin_ctzll(hit);
                 int tok = my_last;
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
 #pragma unroll
                     for (int e = 0; e < C::E; ++e) {
                         c += (double)w[e];
-                        if (!done && c > rem) {
+                        if (!done && w[e] > 0.f && c > rem) {      // never a token outside the residual's support
                             tok = ch * C::E + e;
                             done = true;
                         }

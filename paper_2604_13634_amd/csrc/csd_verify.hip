@@ -177,31 +177,145 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Phase 2: one wave, one sequence (all 64 lanes active on entry).
+// Phase 2: one wave, one sequence (all 64 lanes active on entry).  Lane i < k owns draft position i.
+
+// The draft token of this lane's position and its target logit: independent of the row statistics, so it is
+// fetched before them and the latencies overlap.
+struct DraftLane {
+    int d;
+    bool valid;
+    float zd;
+};
+template <bool SHARDED>
+__device__ __forceinline__ DraftLane load_draft_lane(const EpilogueArgs &a, int b, int lane) {
+    DraftLane dl = {-1, false, 0.f};
+    if (lane < a.k) {
+        dl.d = a.draft[(int64_t)b * a.k + lane];
+        dl.valid = (dl.d >= 0) && (dl.d < a.V);
+        if (dl.valid)
+            dl.zd = SHARDED ? a.draft_logit[(int64_t)b * a.k + lane]
+                            : load_logit(a.logits, a.dtype, ((int64_t)b * (a.k + 1) + lane) * a.row_stride + dl.d);
+    }
+    return dl;
+}
+
+// How the lanes of a wave share the k+1 rows of a sequence: G lanes (a power of two) per row.
+__device__ __forceinline__ int lanes_per_row(int K1) {
+    int G = 1;
+    while (2 * G * K1 <= kWaveSize) G *= 2;
+    return G;
+}
+
+// Row statistics held by the first lane of each row's group -> outputs, and to the position layout
+// (lane i gets the statistics of row i; lanes >= K1 read row 0, unused).
+__device__ __forceinline__ void publish_row_stats(const EpilogueArgs &a, int b, int lane, int G, float gm, int t, double S,
+                                                  float &rmax, int &tstar, double &rS) {
+    const int K1 = a.k + 1;
+    const int grow = lane / G, gs = lane & (G - 1);
+    if (grow < K1 && gs == 0) {
+        const int64_t row = (int64_t)b * K1 + grow;
+        a.argmax[row] = t;
+        if (a.row_max) a.row_max[row] = gm;
+        if (a.row_sumexp) a.row_sumexp[row] = (float)S;
+    }
+    const int src = (lane < K1 ? lane : 0) * G;
+    rmax = from_lane_f(gm, src);
+    tstar = from_lane_i(t, src);
+    rS = from_lane_d(S, src);
+}
+
+// What a lane carries out of the verification loop for the update phase.
+struct Divergence {
+    bool counted;        // this position's pair goes to UpdateMemory
+    uint64_t key;
+    OcmProbe probe;      // where the lookup ended (only when probed)
+};
+
+// Algorithm 1 for one sequence, given its row statistics: ratio (Eq. 3), match, memory lookup, gate, accepted
+// prefix, emitted token, outputs and the per-workgroup status counters.  PROBE: keep where each lookup ended
+// (for updates applied straight from these lanes); the lookup is then made even when lambda == 0.
+template <bool PROBE>
+__device__ __forceinline__ Divergence sequence_decide(const EpilogueArgs &a, int b, int lane, const DraftLane &dl, float rmax,
+                                                      int tstar, double rS, BlockCounters &counters) {
+    const int k = a.k;
+    const bool is_pos = lane < k;
+    const int d = dl.d;
+    const bool valid = dl.valid;
+
+    // ---- Eq. 3: ratio = p(draft)/p(t*) = exp(z_draft - m); p(draft) = ratio / S
+    double ratio = 0.0;
+    if (is_pos) {
+        if (valid) ratio = exp2(((double)dl.zd - (double)rmax) * 1.4426950408889634);
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.ratio) a.ratio[o] = (float)ratio;
+        if (a.p_draft) a.p_draft[o] = (float)(ratio / rS);
+    }
+
+    // ---- Algorithm 1: match, else memory lookup and gate
+    const bool match = is_pos && (d == tstar);
+    const bool diverges = is_pos && valid && !match;
+    Divergence out;
+    out.key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? tstar : 0));
+    out.probe = OcmProbe{0, 0, false, false};
+    bool is_freq = false;
+    if (diverges && a.ocm != nullptr) {
+        if (PROBE) {
+            out.probe = ocm_probe(a.ocm, a.capacity, out.key);
+            is_freq = out.probe.count >= a.lambda;
+        } else {   // lambda == 0 makes every pair frequent without touching the table
+            is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, out.key) >= a.lambda);
+        }
+    }
+    const bool is_safe = diverges && (ratio >= (double)a.tau);
+    const bool ok = match || (is_freq && is_safe);
+
+    // ---- accepted prefix, emitted token, divergences to count (every processed one, rescued or not)
+    const uint64_t fail = __builtin_amdgcn_ballot_w64(is_pos && !ok) | (1ull << k);
+    const int n = (int)__builtin_ctzll(fail);                  // first failing position, k if none
+    const bool processed = is_pos && (lane <= n);
+    const bool counted = processed && diverges;
+    const int next = from_lane_i(tstar, n);                    // row n: stopping position or bonus row
+    out.counted = counted;
+
+    if (is_pos) {
+        const int64_t o = (int64_t)b * k + lane;
+        if (a.pos_flags) {
+            uint8_t f = 0;
+            if (processed) {
+                if (match) f = CSD_POS_MATCH | CSD_POS_ACCEPTED;
+                else if (diverges)
+                    f = CSD_POS_COUNTED | (is_freq ? CSD_POS_FREQ : 0) | (is_safe ? CSD_POS_SAFE : 0) |
+                        (ok ? CSD_POS_ACCEPTED : 0);
+            }
+            a.pos_flags[o] = f;
+        }
+        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? out.key : CSD_OCM_EMPTY);   // read by the update wave
+    }
+    const uint64_t m_counted = __builtin_amdgcn_ballot_w64(counted);
+    const uint64_t m_rescued = __builtin_amdgcn_ballot_w64(counted && ok);
+    const uint64_t m_bad = __builtin_amdgcn_ballot_w64(processed && !valid);
+    if (lane == 0) {
+        a.accept_len[b] = n;
+        a.next_token[b] = next;
+        if (m_bad) atomicAdd(&counters.v[CSD_STATUS_BAD_DRAFT], (unsigned int)__builtin_popcountll(m_bad));
+        if (m_rescued) atomicAdd(&counters.v[CSD_STATUS_RESCUED], (unsigned int)__builtin_popcountll(m_rescued));
+        if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
+        if (n) atomicAdd(&counters.v[CSD_STATUS_ACCEPTED], (unsigned int)n);
+    }
+    return out;
+}
+
+// The sequence's step when the row partials sit in memory from an earlier launch.
 // SHARDED: the row partials come as several sets (vocabulary shards) and the draft logits as an array.
 template <bool SHARDED>
 __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, int lane, BlockCounters &counters) {
-    const int k = a.k, K1 = a.k + 1;
-    const bool is_pos = lane < k;
-
-    // draft token and its logit first: independent of the partials, so the latencies overlap
-    int d = -1;
-    bool valid = false;
-    float zd = 0.f;
-    if (is_pos) {
-        d = a.draft[(int64_t)b * k + lane];
-        valid = (d >= 0) && (d < a.V);
-        if (valid)
-            zd = SHARDED ? a.draft_logit[(int64_t)b * k + lane]
-                         : load_logit(a.logits, a.dtype, ((int64_t)b * K1 + lane) * a.row_stride + d);
-    }
+    const int K1 = a.k + 1;
+    const DraftLane dl = load_draft_lane<SHARDED>(a, b, lane);
 
     // ---- combine the partials: G lanes share a row, then a butterfly inside each group of G
-    int G = 1;
-    while (2 * G * K1 <= kWaveSize) G *= 2;
+    const int G = lanes_per_row(K1);
     const int grow = lane / G, gs = lane & (G - 1);
-    const bool active = grow < K1;
-    const int64_t prow = (int64_t)b * K1 + (active ? grow : 0);
+    const int64_t prow = (int64_t)b * K1 + (grow < K1 ? grow : 0);
     float gm = -INFINITY;
     int t = 0x7fffffff;
     double S = 0.0;
@@ -216,69 +330,11 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
             partials_sum_pass(a.shard_partials[s] + prow * a.shard_per_row[s], a.shard_per_row[s], G, gs, mref, S);
         partials_sum_merge(G, S);
     }
-    if (active && gs == 0) {
-        const int64_t row = (int64_t)b * K1 + grow;
-        a.argmax[row] = t;
-        if (a.row_max) a.row_max[row] = gm;
-        if (a.row_sumexp) a.row_sumexp[row] = (float)S;
-    }
-    // position layout: lane i takes the statistics of row i (lanes >= K1 read row 0, unused)
-    const int src = (lane < K1 ? lane : 0) * G;
-    const float rmax = from_lane_f(gm, src);
-    const int tstar = from_lane_i(t, src);
-    const double rS = from_lane_d(S, src);
-
-    // ---- Eq. 3: ratio = p(draft)/p(t*) = exp(z_draft - m); p(draft) = ratio / S
-    double ratio = 0.0;
-    if (is_pos) {
-        if (valid) ratio = exp2(((double)zd - (double)rmax) * 1.4426950408889634);
-        const int64_t o = (int64_t)b * k + lane;
-        if (a.ratio) a.ratio[o] = (float)ratio;
-        if (a.p_draft) a.p_draft[o] = (float)(ratio / rS);
-    }
-
-    // ---- Algorithm 1: match, else memory lookup and gate
-    const bool match = is_pos && (d == tstar);
-    const bool diverges = is_pos && valid && !match;
-    const uint64_t key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? tstar : 0));
-    bool is_freq = false;
-    if (diverges && a.ocm != nullptr)   // lambda == 0 makes every pair frequent without touching the table
-        is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, key) >= a.lambda);
-    const bool is_safe = diverges && (ratio >= (double)a.tau);
-    const bool ok = match || (is_freq && is_safe);
-
-    // ---- accepted prefix, emitted token, divergences to count (every processed one, rescued or not)
-    const uint64_t fail = __builtin_amdgcn_ballot_w64(is_pos && !ok) | (1ull << k);
-    const int n = (int)__builtin_ctzll(fail);                  // first failing position, k if none
-    const bool processed = is_pos && (lane <= n);
-    const bool counted = processed && diverges;
-    const int next = from_lane_i(tstar, n);                    // row n: stopping position or bonus row
-
-    if (is_pos) {
-        const int64_t o = (int64_t)b * k + lane;
-        if (a.pos_flags) {
-            uint8_t f = 0;
-            if (processed) {
-                if (match) f = CSD_POS_MATCH | CSD_POS_ACCEPTED;
-                else if (diverges)
-                    f = CSD_POS_COUNTED | (is_freq ? CSD_POS_FREQ : 0) | (is_safe ? CSD_POS_SAFE : 0) |
-                        (ok ? CSD_POS_ACCEPTED : 0);
-            }
-            a.pos_flags[o] = f;
-        }
-        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? key : CSD_OCM_EMPTY);   // read by the update wave
-    }
-    const uint64_t m_counted = __builtin_amdgcn_ballot_w64(counted);
-    const uint64_t m_rescued = __builtin_amdgcn_ballot_w64(counted && ok);
-    const uint64_t m_bad = __builtin_amdgcn_ballot_w64(processed && !valid);
-    if (lane == 0) {
-        a.accept_len[b] = n;
-        a.next_token[b] = next;
-        if (m_bad) atomicAdd(&counters.v[CSD_STATUS_BAD_DRAFT], (unsigned int)__builtin_popcountll(m_bad));
-        if (m_rescued) atomicAdd(&counters.v[CSD_STATUS_RESCUED], (unsigned int)__builtin_popcountll(m_rescued));
-        if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
-        if (n) atomicAdd(&counters.v[CSD_STATUS_ACCEPTED], (unsigned int)n);
-    }
+    float rmax;
+    int tstar;
+    double rS;
+    publish_row_stats(a, b, lane, G, gm, t, S, rmax, tstar, rS);
+    sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, counters);
 }
 
 template <int DT>
@@ -314,6 +370,294 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
     apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The whole step in ONE launch.  Workgroups [0, n_stream_wgs) stream the rows exactly as row_partials_kernel
+// does and publish one StepRecord per wave; the workgroups after them take kStepSeqWaves sequences each (one
+// wave per sequence), fetch the draft tokens and their logits at once, wait for the records of their rows,
+// and run the verification loop.  The hardware hands out workgroups of a launch in index order, so a sequence
+// workgroup only ever waits for streaming workgroups that have already been started; its waits are bounded
+// all the same (kSpinLimit polls of about a microsecond each), and a wait that runs out is reported in
+// status[CSD_STATUS_STALLED] instead of hanging.
+//
+// Memory updates: with at most kMaxBarrierWorkgroups sequence workgroups (all resident together, so they can
+// wait for each other) each workgroup counts itself in on the control head once its lookups are done, waits
+// until all have, and then every lane adds its own pair straight to the table at the slot its lookup ended at
+// (ocm_add_one_after_probe): all lookups of the step precede all its updates, and no log is re-read.  Each
+// workgroup counts itself out as well; the last one out resets the counter for the next call.
+constexpr uint32_t kSpinLimit = 1u << 21;
+constexpr int kSpinSleep = 6;                     // s_sleep units of 64 clocks between polls
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+// the check word of a record: a hash of its two data words, of the call's number and of the record's index
+__device__ __forceinline__ uint64_t record_check(uint64_t w0, uint64_t w1, uint64_t nonce, uint64_t rec) {
+    return mix64(w0 + mix64(w1 ^ (nonce + rec * 0x9E3779B97F4A7C15ull))) | 1ull;   // never zero: a zeroed record does not pass
+}
+__device__ __forceinline__ void publish_record(StepRecord *r, uint64_t nonce, uint64_t rec, const RowPartial &p) {
+    const uint64_t w0 = (uint64_t)__float_as_uint(p.m) | ((uint64_t)__float_as_uint(p.cref) << 32);
+    const uint64_t w1 = (uint64_t)__float_as_uint(p.s) | ((uint64_t)(uint32_t)p.idx << 32);
+    xwg_store64(&r->w0, w0);
+    xwg_store64(&r->w1, w1);
+    xwg_store64(&r->check, record_check(w0, w1, nonce, rec));
+}
+
+// Records j = gs + u*G (u0 <= u < u0 + 4) of one row: loaded until they pass, four at a time.  `want` says
+// which of the four this lane needs; passing ones are decoded into q and their check word zeroed.
+// Returns false when the wait ran out.  Called by all lanes of the wave together.
+__device__ __forceinline__ bool acquire_four_records(StepRecord *row_rec, uint64_t rec0, int G, int gs, int u0, uint32_t want,
+                                                     uint64_t nonce, RowPartial (&q)[4]) {
+    uint32_t pend = want;
+    for (uint32_t spin = 0;; ++spin) {
+        uint64_t w0[4], w1[4], ck[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((pend >> u) & 1u) {
+                const StepRecord *r = row_rec + gs + (u0 + u) * G;
+                w0[u] = xwg_load64(&r->w0);
+                w1[u] = xwg_load64(&r->w1);
+                ck[u] = xwg_load64(&r->check);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((pend >> u) & 1u) {
+                const uint64_t j = (uint64_t)(gs + (u0 + u) * G);
+                if (ck[u] == record_check(w0[u], w1[u], nonce, rec0 + j)) {
+                    q[u].m = __uint_as_float((uint32_t)w0[u]);
+                    q[u].cref = __uint_as_float((uint32_t)(w0[u] >> 32));
+                    q[u].s = __uint_as_float((uint32_t)w1[u]);
+                    q[u].idx = (int32_t)(uint32_t)(w1[u] >> 32);
+                    xwg_store64(&row_rec[gs + (u0 + u) * G].check, 0ull);
+                    pend &= ~(1u << u);
+                }
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(pend != 0u) == 0ull) return true;
+        if (spin >= kSpinLimit) return false;
+        __builtin_amdgcn_s_sleep(kSpinSleep);
+    }
+}
+
+// All records of this lane's share of its row -> (m, t*, S) of the row, in the first lane of its group.  The
+// maximum and its lowest id are folded as the records come in (in index order); the NB (cref, s) pairs are kept
+// for the sum against the row maximum.  The arithmetic, and its order, are those of the two-launch combine.
+template <int NB>
+__device__ __forceinline__ bool acquire_row_stats(StepRecord *row_rec, uint64_t rec0, int P, int G, int gs, bool active,
+                                                  uint64_t nonce, float &gm, int &t, double &S) {
+    float cref[NB], sv[NB];
+    bool ok = true;
+    gm = -INFINITY;
+    t = 0x7fffffff;
+    S = 0.0;
+#pragma unroll
+    for (int u0 = 0; u0 < NB; u0 += 4) {
+        RowPartial q4[4];
+        uint32_t want = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            q4[u] = empty_partial();
+            if (active && gs + (u0 + u) * G < P) want |= 1u << u;
+        }
+        if (__builtin_amdgcn_ballot_w64(want != 0u) != 0ull) ok = acquire_four_records(row_rec, rec0, G, gs, u0, want, nonce, q4) && ok;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (q4[u].m > gm || (q4[u].m == gm && q4[u].idx < t)) t = q4[u].idx;
+            gm = fmaxf(gm, q4[u].m);
+            cref[u0 + u] = q4[u].cref;
+            sv[u0 + u] = q4[u].s;
+        }
+    }
+    partials_max_merge(G, gm, t);
+    const double mref = (double)gm * kLog2eD;                  // exact: two 24-bit significands
+#pragma unroll
+    for (int u = 0; u < NB; ++u)
+        if (sv[u] != 0.f) S += (double)sv[u] * (double)__builtin_amdgcn_exp2f((float)((double)cref[u] - mref));
+    partials_sum_merge(G, S);
+    return ok;
+}
+
+__device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCounters &counters, int *verdict) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wg = (int)blockIdx.x - a.n_stream_wgs;
+    const int n_seq_wgs = (int)gridDim.x - a.n_stream_wgs;
+    const int b = wg * kStepSeqWaves + (threadIdx.x >> 6);
+    const int k = a.k, K1 = a.k + 1;
+    // thread 0 will need the control head set up: ask early, look at the answer late
+    uint64_t magic = 0;
+    if (a.update_here && threadIdx.x == 0) magic = xwg_load64(&a.ctrl->magic);
+    block_counters_clear(counters);
+
+    Divergence dv;
+    dv.counted = false;
+    dv.key = 0;
+    dv.probe = OcmProbe{0, 0, false, false};
+    bool stalled = false;
+    if (b < a.B) {                                   // wave-uniform: a wave takes a sequence or none
+        const DraftLane dl = load_draft_lane<false>(a, b, lane);
+        const int P = a.shard_per_row[0];
+        const int G = lanes_per_row(K1);
+        const int grow = lane / G, gs = lane & (G - 1);
+        const bool active = grow < K1;
+        const int64_t prow = (int64_t)b * K1 + (active ? grow : 0);
+        StepRecord *row_rec = a.records + prow * P;
+        const uint64_t rec0 = (uint64_t)prow * (uint64_t)P;
+        const int per_lane = (P + G - 1) / G;        // wave-uniform
+        // Rows are streamed in index order, so the records of the bonus row's last wave are among the last of
+        // this sequence to arrive: wait for that one record first (one lane, one 32-byte line per poll) and only
+        // then for all of them - hundreds of lanes polling every record of rows that are still being streamed take
+        // bandwidth from the very workgroups they are waiting for.
+        {
+            const uint64_t rs = ((uint64_t)b * K1 + k) * (uint64_t)P + (uint64_t)(P - 1);
+            const StepRecord *sr = a.records + rs;
+            for (uint32_t spin = 0; spin < kSpinLimit; ++spin) {
+                int seen = 0;
+                if (lane == 0) {
+                    const uint64_t w0 = xwg_load64(&sr->w0), w1 = xwg_load64(&sr->w1), ck = xwg_load64(&sr->check);
+                    seen = (ck == record_check(w0, w1, a.nonce, rs)) ? 1 : 0;
+                }
+                if (__builtin_amdgcn_readfirstlane(seen)) break;
+                __builtin_amdgcn_s_sleep(kSpinSleep);
+            }
+        }
+        float gm;
+        int t;
+        double S;
+        bool ok;
+        if (per_lane <= 4) {
+            ok = acquire_row_stats<4>(row_rec, rec0, P, G, gs, active, a.nonce, gm, t, S);
+        } else if (per_lane <= 12) {
+            ok = acquire_row_stats<12>(row_rec, rec0, P, G, gs, active, a.nonce, gm, t, S);
+        } else {
+            // many partials per lane (a huge vocabulary under a small batch): wait for them four at a time, keeping
+            // the running maximum only, then take the sums in a second pass over the (now plainly readable) words
+            ok = true;
+            gm = -INFINITY;
+            t = 0x7fffffff;
+            S = 0.0;
+            for (int u0 = 0; u0 < per_lane; u0 += 4) {
+                RowPartial q4[4];
+                uint32_t want = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    q4[u] = empty_partial();
+                    if (active && gs + (u0 + u) * G < P) want |= 1u << u;
+                }
+                if (__builtin_amdgcn_ballot_w64(want != 0u) != 0ull)
+                    ok = acquire_four_records(row_rec, rec0, G, gs, u0, want, a.nonce, q4) && ok;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (q4[u].m > gm || (q4[u].m == gm && q4[u].idx < t)) t = q4[u].idx;
+                    gm = fmaxf(gm, q4[u].m);
+                }
+            }
+            partials_max_merge(G, gm, t);
+            const double mref = (double)gm * kLog2eD;
+            if (active) {
+                for (int j = gs; j < P; j += G) {
+                    const uint64_t w0 = xwg_load64(&row_rec[j].w0), w1 = xwg_load64(&row_rec[j].w1);
+                    const float cref = __uint_as_float((uint32_t)(w0 >> 32)), sj = __uint_as_float((uint32_t)w1);
+                    if (sj != 0.f) S += (double)sj * (double)__builtin_amdgcn_exp2f((float)((double)cref - mref));
+                }
+            }
+            partials_sum_merge(G, S);
+        }
+        stalled = !ok;
+        if (!stalled) {
+            float rmax;
+            int tstar;
+            double rS;
+            publish_row_stats(a, b, lane, G, gm, t, S, rmax, tstar, rS);
+            if (a.update_here) dv = sequence_decide<true>(a, b, lane, dl, rmax, tstar, rS, counters);
+            else dv = sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, counters);
+        } else if (lane == 0) {                      // the records never came: say so, and report nothing as accepted
+            a.accept_len[b] = 0;
+            a.next_token[b] = -1;
+            atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
+        }
+    }
+
+    // The step's counters leave now (all but the rare lost insert are known): their atomics need no answer
+    // and travel while the workgroup waits below.
+    barrier_lds_only();
+    if (a.status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
+        atomicAdd(&a.status[threadIdx.x], counters.v[threadIdx.x]);
+
+    if (a.update_here) {
+        // An absent pair's slot is claimed at once (count zero: no lookup of the step reads it differently); the
+        // compare-and-swap is in flight during the barrier below.
+        OcmClaim claim = {CSD_OCM_EMPTY, false, false};
+        if (dv.counted) claim = ocm_claim_after_probe(a.ocm, dv.key, dv.probe);
+        // ---- barrier among the sequence workgroups: every lookup of the step before any update of the step.
+        // This workgroup's lookups have returned (their values were used above); its stores may still be on their
+        // way, nobody waits for them.
+        if (threadIdx.x == 0) {
+            bool good = true;
+            for (uint32_t spin = 0; magic != kStepMagic; ++spin) {           // set up by workgroup 0 of this launch at the latest
+                if (spin >= kSpinLimit) { good = false; break; }
+                __builtin_amdgcn_s_sleep(kSpinSleep);
+                magic = xwg_load64(&a.ctrl->magic);
+            }
+            const uint32_t total = (uint32_t)n_seq_wgs;
+            if (good) {
+                __hip_atomic_fetch_add(&a.ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (uint32_t spin = 0;; ++spin) {
+                    if (__hip_atomic_load(&a.ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
+                    if (spin >= kSpinLimit) { good = false; break; }
+                    __builtin_amdgcn_s_sleep(kSpinSleep);
+                }
+            }
+            if (!good && a.status != nullptr) atomicAdd(&a.status[CSD_STATUS_STALLED], 1u);
+            *verdict = good ? (int)total : 0;
+        }
+        barrier_lds_only();
+        const int passed = *verdict;
+        if (passed != 0 && dv.counted) {
+            if (!ocm_add_one_after_claim(a.ocm, a.capacity, dv.key, dv.probe, claim) && a.status != nullptr)
+                atomicAdd(&a.status[CSD_STATUS_DROPPED], 1u);
+        }
+        if (threadIdx.x == 0 && passed != 0) {
+            // counted out, off the updates' path: the workgroup that brings the counter to 2 * total is the last to
+            // have read it, and leaves it at zero for the next call
+            const uint32_t total = (uint32_t)passed;
+            const uint32_t old = __hip_atomic_fetch_add(&a.ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == 2u * total - 1u) __hip_atomic_store(&a.ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void verify_step_kernel(StreamSource src, int V, int nsplit,
+                                                                                 EpilogueArgs a) {
+    __shared__ BlockCounters counters;
+    __shared__ int verdict;
+    if ((int)blockIdx.x >= a.n_stream_wgs) {
+        step_sequences(a, counters, &verdict);
+        return;
+    }
+    const int row = blockIdx.x / nsplit;
+    const int split = blockIdx.x - row * nsplit;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0 && xwg_load64(&a.ctrl->magic) != kStepMagic) {
+        // first use of this workspace: the counter starts at zero, and only then does the magic say so
+        __hip_atomic_store(&a.ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the zero is acknowledged before the magic leaves
+        xwg_store64(&a.ctrl->magic, kStepMagic);
+    }
+    const char *rowp = src.base0 + (int64_t)row * src.pitch0;
+    const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
+    if (lane == 0) {
+        const uint64_t rec = ((uint64_t)row * nsplit + split) * kStreamWaves + wave;
+        publish_record(a.records + rec, a.nonce, rec, out);
+    }
+}
+
 }  // namespace
 
 StreamPlan make_stream_plan(int rows, int V, int dtype) {
@@ -335,9 +679,9 @@ StreamPlan make_stream_plan(int rows, int V, int dtype) {
 
 WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
     WorkspaceLayout w;
-    w.ticket_off = 0;                              // one uint32, written by kernel 1, drawn in kernel 2
+    w.ticket_off = 0;
     w.partials_off = 256;
-    w.partials_bytes = (size_t)p.rows * (size_t)p.partials_per_row * sizeof(RowPartial);
+    w.partials_bytes = (size_t)p.rows * (size_t)p.partials_per_row * sizeof(StepRecord);
     w.log_off = (w.partials_off + w.partials_bytes + 255) & ~(size_t)255;
     w.log_bytes = (size_t)B * (size_t)k * sizeof(uint64_t);
     w.total = (w.log_off + w.log_bytes + 255) & ~(size_t)255;
@@ -383,6 +727,18 @@ hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(shard_draft_logits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, logits, dtype,
                        row_stride, B, k, V_shard, base, draft, draft_logit);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_step(const StreamSource &src, int dtype, int V, const StreamPlan &plan, const EpilogueArgs &a,
+                              hipStream_t stream) {
+    if (plan.rows == 0 || a.B == 0) return hipSuccess;
+    const int n_seq_wgs = (a.B + kStepSeqWaves - 1) / kStepSeqWaves;
+    const dim3 grid((unsigned)(a.n_stream_wgs + n_seq_wgs)), block(kStreamWaves * kWaveSize);
+    if (dtype == CSD_DTYPE_F32)
+        hipLaunchKernelGGL(verify_step_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, src, V, plan.nsplit, a);
+    else
+        hipLaunchKernelGGL(verify_step_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, src, V, plan.nsplit, a);
     return hipGetLastError();
 }
 

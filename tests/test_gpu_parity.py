@@ -47,6 +47,17 @@ def test_full_size_steps_with_prior(ci, steps):
     assert rescued > 0
 
 
+@pytest.mark.parametrize("ci,steps", [(1, 400), (2, 150), (3, 80), (4, 80)])
+def test_full_size_streams_from_an_empty_memory(ci, steps):
+    """Configs 1-4 at full size (the shapes and launch configuration bench.py times), the memory evolving
+    from empty: pairs cross the frequency threshold and are rescued without any prior.  Every step is
+    compared, the memory every 10 steps."""
+    w = Workload(CONFIGS[ci])
+    orc, ocm, rescued, counted = run_stream(w, range(steps), check_table_every=10, threads=16)
+    print("%s: %d steps from empty, %d rescued, %d counted, %d pairs" % (w.cfg.name, steps, rescued, counted, len(orc.T)))
+    assert rescued > 0 and counted > steps
+
+
 @pytest.mark.skipif(os.environ.get("CSD_FULL_STREAMS") != "1",
                     reason="several minutes of oracle time per configuration: set CSD_FULL_STREAMS=1 and run with -s")
 @pytest.mark.parametrize("ci", [1, 2, 3, 4])
@@ -228,6 +239,34 @@ def test_deferred_updates_through_rejection_log():
         compare_step(res, bfb, "deferred step %d" % step)
     compare_table(ocm_a, orc)
     compare_table(ocm_b, orc)
+
+
+def test_in_kernel_updates_equal_replayed_log_at_full_batch():
+    """The hand-over of the step log to the workgroup that applies it, at the contention workload's batch
+    (256 sequences, 16 workgroups in the finish kernel): over 150 steps, a memory updated inside csd_verify
+    and one updated by replaying each step's rej_log through csd_ocm_update stay identical, and so do all
+    outputs (a log entry that the applying workgroup read too early would lose a count)."""
+    w = Workload(CONFIGS[4], V=4096 + 6)
+    cfg = w.cfg
+    ocm_a, ocm_b = csd.new_ocm(1 << 14), csd.new_ocm(1 << 14)
+    bfa = bfb = None
+    inputs = []
+    for step in range(12):                              # twelve distinct steps, cycled: the counts keep growing
+        z, draft = w.step(step, threads=8)
+        inputs.append((to_device_logits(z), torch.from_numpy(draft).cuda()))
+    for step in range(150):
+        zt, dt = inputs[step % len(inputs)]
+        bfa = csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm_a, csd.CSD_APPLY_UPDATES, buffers=bfa)
+        bfb = csd.csd_verify(zt, dt, cfg.tau, cfg.lam, ocm_b, 0, buffers=bfb)
+        csd.csd_ocm_update(ocm_b, bfb.rej_log.view(-1), status=bfb.status)
+        torch.cuda.synchronize()
+        for name in ("accept_len", "next_token", "argmax", "pos_flags", "rej_log"):
+            assert torch.equal(getattr(bfa, name), getattr(bfb, name)), "step %d %s" % (step, name)
+        if step % 10 == 0 or step == 149:
+            assert decode_ocm(ocm_a) == decode_ocm(ocm_b), "memories differ at step %d" % step
+    st = bfa.status.cpu().numpy().view(np.uint32)
+    assert st[csd.CSD_STATUS_RESCUED] > 1000 and sum(decode_ocm(ocm_a).values()) == st[csd.CSD_STATUS_COUNTED]
+    assert torch.equal(bfa.status, bfb.status)
 
 
 @pytest.mark.parametrize("B", [300, 700, 2200])
