@@ -212,13 +212,20 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
  *   keys     [n] CSD_OCM_KEY(draft, target); bits above the key field are ignored; entries equal to
  *            CSD_OCM_EMPTY in the key field are skipped (so a rej_log can be passed as is).
  *   weights  [n] increments (uint32), or NULL = 1 each.  Zero weights are skipped.
- *   n        number of entries, 0 is a no-op.
+ *   n        number of entries (the size of the arrays), 0 is a no-op.
+ *   n_dev    NULL, or a DEVICE uint64 holding the number of entries to apply when the call runs: min(n, *n_dev)
+ *            are taken.  A list whose length only the device knows - csd_ocm_export's n_out, the reload of a
+ *            checkpointed prior, a replica's pairs being folded in - is applied without a host synchronisation,
+ *            also from inside a captured graph.
  * Duplicate keys are summed; counts saturate at CSD_OCM_COUNT_MAX; status as for csd_verify (nullable).
  */
 int csd_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
-                   uint32_t *status, void *stream);
+                   const uint64_t *n_dev, uint32_t *status, void *stream);
 
-/* csd_ocm_reset - set every slot to CSD_OCM_EMPTY (the empty memory an uncalibrated run starts from). */
+/*
+ * csd_ocm_reset - set every slot to CSD_OCM_EMPTY: the empty memory of a run without prior calibration (the
+ * starting point of the paper's sensitivity study of online updates alone), and the first step of growing a table.
+ */
 int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream);
 
 /*
@@ -239,8 +246,9 @@ int csd_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uin
                   void *stream);
 
 /*
- * csd_ocm_export - the table as a compact list, layout-independent (what a checkpoint or an exchange
- * between devices carries): keys_out[j] = CSD_OCM_KEY(draft, target), counts_out[j] = its count, for the
+ * csd_ocm_export - the table as a compact list, layout-independent.  Prior calibration (Online Correction
+ * Memory, phase 1) is a one-time, offline product that deployments start from: this is the form it is kept in
+ * (a checkpoint) or sent in (between devices): keys_out[j] = CSD_OCM_KEY(draft, target), counts_out[j] = its count, for the
  * n pairs the table holds, in unspecified order.  *n_out (device, uint64) receives n; when n exceeds
  * max_entries only max_entries pairs are written.  keys_out / counts_out may be NULL with max_entries == 0
  * (count only).  The list can be fed back through csd_ocm_update(keys, counts).
@@ -281,7 +289,8 @@ int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows
 
 /*
  * Vocabulary shards.  When the target's logits exist only as shards of the vocabulary - a tensor-parallel
- * LM head (the large targets span several devices), or a head evaluated chunk by chunk - each shard runs
+ * LM head (Implementation Details: each 70B-class target spans two devices), or a head evaluated chunk by
+ * chunk - each shard runs
  * csd_row_partials on its [B*(k+1)][V_s] slice and csd_shard_draft_logits to pick out the logits of the
  * draft tokens it owns; the partials (16 bytes each) and the [B][k] draft logits are all that has to be
  * brought together, and csd_verify_shards does the rest of the step from them: the same combine, lookup,

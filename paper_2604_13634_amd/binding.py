@@ -75,7 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.csd_shard_draft_logits.restype = i32
     lib.csd_shard_draft_logits.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp, vp, vp]
     lib.csd_ocm_update.restype = i32
-    lib.csd_ocm_update.argtypes = [vp, u64, vp, vp, u64, vp, vp]
+    lib.csd_ocm_update.argtypes = [vp, u64, vp, vp, u64, vp, vp, vp]
     lib.csd_ocm_reset.restype = i32
     lib.csd_ocm_reset.argtypes = [vp, u64, vp]
     lib.csd_ocm_lookup.restype = i32
@@ -350,15 +350,18 @@ def csd_verify_sampled(target_logits: torch.Tensor, draft_logits: torch.Tensor, 
 
 
 def csd_ocm_update(ocm: torch.Tensor, keys: torch.Tensor, weights: Optional[torch.Tensor] = None,
-                   status: Optional[torch.Tensor] = None, stream=None) -> None:
-    """T[key] += weight for every entry (keys: int64 CSD_OCM_KEY values; weights: int32 or None = 1)."""
+                   status: Optional[torch.Tensor] = None, stream=None, n_dev: Optional[torch.Tensor] = None) -> None:
+    """T[key] += weight for every entry (keys: int64 CSD_OCM_KEY values; weights: int32 or None = 1).
+    n_dev: optional int64 device tensor [1]; only the first min(len(keys), n_dev) entries are applied."""
+    if n_dev is not None and (n_dev.dtype != torch.int64 or n_dev.numel() != 1):
+        raise ValueError("n_dev must be an int64 tensor with one element")
     if keys.dtype != torch.int64 or not keys.is_contiguous():
         raise ValueError("keys must be contiguous int64")
     if weights is not None and (weights.dtype != torch.int32 or weights.numel() != keys.numel()
                                 or not weights.is_contiguous()):
         raise ValueError("weights must be contiguous int32, one per key")
-    rc = load_library().csd_ocm_update(_ptr(ocm), ocm.numel(), _ptr(keys), _ptr(weights), keys.numel(), _ptr(status),
-                                       _stream(stream))
+    rc = load_library().csd_ocm_update(_ptr(ocm), ocm.numel(), _ptr(keys), _ptr(weights), keys.numel(), _ptr(n_dev),
+                                       _ptr(status), _stream(stream))
     if rc != CSD_OK:
         raise CsdError(rc, "csd_ocm_update")
 
@@ -384,14 +387,18 @@ def csd_ocm_merge(dst: torch.Tensor, src: torch.Tensor, status: Optional[torch.T
         raise CsdError(rc, "csd_ocm_merge")
 
 
-def csd_ocm_export(ocm: torch.Tensor, max_entries: Optional[int] = None, stream=None):
+def csd_ocm_export(ocm: torch.Tensor, max_entries: Optional[int] = None, stream=None, out=None):
     """Enqueue the export; returns (keys int64 [max_entries], counts int32 [max_entries], n int64 [1]) on the device.
-    Entries beyond n are unwritten."""
-    if max_entries is None:
-        max_entries = ocm.numel()
-    keys = torch.empty((max_entries,), dtype=torch.int64, device=ocm.device)
-    counts = torch.empty((max_entries,), dtype=torch.int32, device=ocm.device)
-    n = torch.empty((1,), dtype=torch.int64, device=ocm.device)
+    Entries beyond n are unwritten.  out: the three tensors to write into (nothing is allocated then)."""
+    if out is not None:
+        keys, counts, n = out
+        max_entries = keys.numel()
+    else:
+        if max_entries is None:
+            max_entries = ocm.numel()
+        keys = torch.empty((max_entries,), dtype=torch.int64, device=ocm.device)
+        counts = torch.empty((max_entries,), dtype=torch.int32, device=ocm.device)
+        n = torch.empty((1,), dtype=torch.int64, device=ocm.device)
     rc = load_library().csd_ocm_export(_ptr(ocm), ocm.numel(), _ptr(keys) if max_entries else None,
                                        _ptr(counts) if max_entries else None, max_entries, _ptr(n), _stream(stream))
     if rc != CSD_OK:

@@ -9,6 +9,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcsd.so")
 SOURCES = ["csd_verify.hip", "csd_sampled.hip", "csd_ocm.hip", "csd_api.hip"]
+PROBE_LIB = os.path.join(PKG, "libcsd_probe.so")
+PROBE_SOURCES = ["read_probe.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -20,11 +22,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2604_13634_amd/libcsd.so; returns its path."""
+def _hipcc(sources, lib: str, verbose: bool) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", LIB]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", lib]
+    cmd += [os.path.join(CSRC, s) for s in sources]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -33,8 +34,19 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return lib
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every HIP source of the verification library into paper_2604_13634_amd/libcsd.so; returns its path."""
+    return _hipcc(SOURCES, LIB, verbose)
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Compile the benchmark's read-only bandwidth probe into its own small library (not part of the C ABI)."""
+    return _hipcc(PROBE_SOURCES, PROBE_LIB, verbose)
 
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe(verbose=True))

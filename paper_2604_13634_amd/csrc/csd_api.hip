@@ -138,7 +138,7 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, plan.rows, nullptr, 0, CSD_LOG2E_F32};
     if (launch_verify_step(src, dtype, V, plan, a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_here) {
-        if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess) return CSD_EHIP;
+        if (launch_ocm_update(ocm, capacity, log, nullptr, (uint64_t)B * (uint64_t)k, nullptr, status, st) != hipSuccess) return CSD_EHIP;
     }
     return CSD_OK;
 }
@@ -241,7 +241,7 @@ int csd_verify_shards(int n_shards, const csd_row_partial *const *shard_partials
     if (update_in_finish && launch_zero_ticket(a.batch_ticket, st) != hipSuccess) return CSD_EHIP;
     if (launch_finish(a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_in_finish) {
-        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess)
+        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, nullptr, status, st) != hipSuccess)
             return CSD_EHIP;
     }
     return CSD_OK;
@@ -364,19 +364,19 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
         return CSD_EHIP;
     if (launch_sampled_tail(a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_in_finish) {
-        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, status, st) != hipSuccess)
+        if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, nullptr, status, st) != hipSuccess)
             return CSD_EHIP;
     }
     return CSD_OK;
 }
 
 int csd_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
-                   uint32_t *status, void *stream) {
+                   const uint64_t *n_dev, uint32_t *status, void *stream) {
     if (!ocm || !is_pow2(capacity)) return CSD_EINVAL;
     if (n == 0) return CSD_OK;
     if (!keys || n > ((uint64_t)1 << 40)) return CSD_EINVAL;
-    if (!aligned(ocm, 8) || !aligned(keys, 8) || !aligned(weights, 4) || !aligned(status, 4)) return CSD_EALIGN;
-    return launch_ocm_update(ocm, capacity, keys, weights, n, status, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+    if (!aligned(ocm, 8) || !aligned(keys, 8) || !aligned(weights, 4) || !aligned(n_dev, 8) || !aligned(status, 4)) return CSD_EALIGN;
+    return launch_ocm_update(ocm, capacity, keys, weights, n, n_dev, status, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
 int csd_ocm_reset(uint64_t *ocm, uint64_t capacity, void *stream) {

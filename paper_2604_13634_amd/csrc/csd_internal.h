@@ -180,7 +180,7 @@ hipError_t launch_zero_ticket(uint32_t *ticket, hipStream_t stream);
 hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_stride, int B, int k, int V_shard, int base,
                                      const int32_t *draft, float *draft_logit, hipStream_t stream);
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
-                             uint32_t *status, hipStream_t stream);
+                             const uint64_t *n_dev, uint32_t *status, hipStream_t stream);
 hipError_t launch_ocm_reset(uint64_t *ocm, uint64_t capacity, hipStream_t stream);
 hipError_t launch_ocm_merge(uint64_t *dst, uint64_t dst_capacity, const uint64_t *src, uint64_t src_capacity,
                             uint32_t *status, hipStream_t stream);

@@ -12,8 +12,12 @@ constexpr unsigned kUpdateGrid = 1024;
 __global__ __launch_bounds__(kApplyThreads) void ocm_update_kernel(uint64_t *ocm, uint64_t capacity,
                                                                    const uint64_t *__restrict__ keys,
                                                                    const uint32_t *__restrict__ weights, uint64_t n,
-                                                                   uint32_t *status) {
+                                                                   const uint64_t *__restrict__ n_dev, uint32_t *status) {
     __shared__ ApplyLds lds;
+    if (n_dev != nullptr) {                         // the list's length as the device knows it, never beyond the arrays
+        const uint64_t nd = *n_dev;
+        n = nd < n ? nd : n;
+    }
     auto fetch = [&](uint64_t e, uint64_t &key, uint32_t &w) {
         key = keys[e] & CSD_OCM_KEY_MASK;
         w = weights ? weights[e] : 1u;
@@ -115,12 +119,12 @@ hipError_t launch_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *k
 }
 
 hipError_t launch_ocm_update(uint64_t *ocm, uint64_t capacity, const uint64_t *keys, const uint32_t *weights, uint64_t n,
-                             uint32_t *status, hipStream_t stream) {
+                             const uint64_t *n_dev, uint32_t *status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     uint64_t blocks = (n + kApplyBatch - 1) / kApplyBatch;
     if (blocks > kUpdateGrid) blocks = kUpdateGrid;
     hipLaunchKernelGGL(ocm_update_kernel, dim3((unsigned)blocks), dim3(kApplyThreads), 0, stream, ocm, capacity, keys, weights, n,
-                       status);
+                       n_dev, status);
     return hipGetLastError();
 }
 

@@ -88,9 +88,10 @@ def test_argument_errors_are_synchronous_and_enqueue_nothing():
 
     assert lib.csd_ocm_reset(None, 1024, None) == b.CSD_EINVAL
     assert lib.csd_ocm_reset(P(good), 1000, None) == b.CSD_EINVAL
-    assert lib.csd_ocm_update(P(good), 1024, None, None, 5, None, None) == b.CSD_EINVAL
-    assert lib.csd_ocm_update(P(good), 1024, None, None, 0, None, None) == b.CSD_OK
-    assert lib.csd_ocm_update(P(good), 1024, P(good + 1), None, 5, None, None) == b.CSD_EALIGN
+    assert lib.csd_ocm_update(P(good), 1024, None, None, 5, None, None, None) == b.CSD_EINVAL
+    assert lib.csd_ocm_update(P(good), 1024, None, None, 0, None, None, None) == b.CSD_OK
+    assert lib.csd_ocm_update(P(good), 1024, P(good + 1), None, 5, None, None, None) == b.CSD_EALIGN
+    assert lib.csd_ocm_update(P(good), 1024, P(good), None, 5, P(good + 4), None, None) == b.CSD_EALIGN
     assert lib.csd_ocm_lookup(P(good), 1024, P(good), None, 5, None) == b.CSD_EINVAL
     assert lib.csd_ocm_lookup(P(good), 3, P(good), P(good), 5, None) == b.CSD_EINVAL
     assert lib.csd_ocm_merge(P(good), 1024, P(good + 0x10000), 1000, None, None) == b.CSD_EINVAL

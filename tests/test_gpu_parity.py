@@ -433,6 +433,63 @@ def test_ocm_merge_export_rehash_roundtrip():
     assert decode_ocm(sat) == {(5, 6): csd.CSD_OCM_COUNT_MAX}
 
 
+def test_exported_list_reloads_by_its_device_side_length():
+    """csd_ocm_export leaves the list's length on the device; csd_ocm_update takes it from there (n_dev), so a
+    memory is copied, grown or folded without the host ever learning the length - eagerly, and replayed from a
+    captured graph while the source memory keeps changing between replays."""
+    rng = np.random.default_rng(77)
+    orc = O.CSDOracle()
+    src = csd.new_ocm(1 << 13)
+
+    def grow_source(n):
+        d = rng.integers(0, 2000, size=n)
+        t = (d + 1 + rng.integers(0, 30, size=n)) % 2000
+        keep = d != t
+        d, t = d[keep], t[keep]
+        wts = rng.integers(1, 50, size=d.size).astype(np.int32)
+        orc.ocm_update(zip(d.tolist(), t.tolist()), wts.tolist())
+        csd.csd_ocm_update(src, torch.from_numpy((d.astype(np.int64) << 20) | t.astype(np.int64)).cuda(), torch.from_numpy(wts).cuda())
+
+    grow_source(3000)
+    cap = src.numel()
+    bufs = (torch.empty(cap, dtype=torch.int64, device="cuda"), torch.empty(cap, dtype=torch.int32, device="cuda"),
+            torch.empty(1, dtype=torch.int64, device="cuda"))
+    # eager: export, then reload into a larger table; the host never reads n
+    dst = csd.new_ocm(1 << 15)
+    keys, counts, n = csd.csd_ocm_export(src, out=bufs)
+    csd.csd_ocm_update(dst, keys, counts, n_dev=n)
+    torch.cuda.synchronize()
+    compare_table(dst, orc, "reloaded by device-side length")
+    # the device-side length never reaches past the arrays handed in
+    few = csd.new_ocm(1 << 10)
+    csd.csd_ocm_update(few, keys[:100], counts[:100], n_dev=n)
+    assert len(decode_ocm(few)) == 100
+    zero = torch.zeros(1, dtype=torch.int64, device="cuda")
+    csd.csd_ocm_update(few, keys, counts, n_dev=zero)
+    assert len(decode_ocm(few)) == 100
+    # captured: reset the copy, export the source, reload - replayed while the source grows
+    copy = csd.new_ocm(1 << 14)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        csd.csd_ocm_reset(copy)
+        csd.csd_ocm_export(src, out=bufs)
+        csd.csd_ocm_update(copy, bufs[0], bufs[1], n_dev=bufs[2])
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        csd.csd_ocm_reset(copy)
+        csd.csd_ocm_export(src, out=bufs)
+        csd.csd_ocm_update(copy, bufs[0], bufs[1], n_dev=bufs[2])
+    for rep in range(4):
+        g.replay()
+        torch.cuda.synchronize()
+        compare_table(copy, orc, "graph replay %d" % rep)
+        grow_source(500)                                # eager work between the replays: the list gets longer
+    assert len(orc.T) > 3000
+
+
 def test_two_streams_share_one_memory():
     """Concurrent verification calls on one table (each with its own buffers and stream): counts stay
     exact.  With a threshold no count can reach, no lookup can change an outcome, so the result is the
