@@ -21,8 +21,9 @@ Batches read the memory as it stood when the step began and add their counts aft
 greedy oracle (csd_oracle.py), whose table class is reused here.
 
 Conventions where the paper is silent: "r <= alpha" is inclusive as printed; a draft id outside [0, V)
-ends the loop uncounted; when the residual has no mass at all (p_i == q_i in floating point, which
-the acceptance test makes a probability-zero branch) t* is the target row's lowest-id argmax.
+ends the loop uncounted; when the residual has no mass at all (p_i == q_i in floating point) t* is the
+target row's lowest-id argmax - a branch no r in [0, 1] reaches, because alpha is then 1 and the token is
+accepted; it is there so that an r outside the range still gives a defined answer.
 """
 from __future__ import annotations
 

@@ -111,35 +111,111 @@ def run_stream(workload, steps, tau=None, lam=None, capacity=None, prior=None, c
 from oracle import csd_oracle_sampled as OS   # noqa: E402
 
 TOL_ACCEPT = 1e-4      # |r - alpha| of every acceptance test
-TOL_DRAW = 1e-5        # probability mass between u * R and the nearer end of the drawn token's interval
+TOL_DRAW = 1e-5        # probability mass: a draw whose u * R lies this close to a boundary of the running sum may
+                       # fall on either side in float32 (the kernel's running sums are good to about 1e-6 of mass)
 
 
 def settle_uniforms(zp, zq, draft, T, u_accept, u_draw, seed, tries=12):
-    """Move the step's random numbers away from decision boundaries, so that a float32 evaluation and the
-    float64 oracle must agree: every |r - alpha| >= TOL_ACCEPT, every draw at least TOL_DRAW of probability
-    mass inside its token's interval.  Offending numbers are re-drawn; a rejected position whose residual is
-    too finely divided for any draw to have that margin (mass spread over thousands of tail tokens) is
-    turned into an accepted one (r = 0).  Returns float32 copies."""
+    """Move the acceptance numbers r away from their decision boundary, |r - alpha| >= TOL_ACCEPT, so that a
+    float32 evaluation and the float64 oracle must agree on every acceptance test; offending numbers are re-drawn
+    (always possible: alpha is one point of [0, 1]).  The draws u_draw are left exactly as generated, however
+    finely the residual is divided: check_sampled_step deals with draws near a boundary.  Returns float32 copies."""
     rng = np.random.default_rng(seed)
     ua, ud = u_accept.astype(np.float32).copy(), u_draw.astype(np.float32).copy()
-    B, k = draft.shape
     V = zp.shape[-1]
     valid = (draft >= 0) & (draft < V)
     for attempt in range(tries + 1):
         r = OS.verify_step_sampled(O.CSDOracle(), zp, zq, draft, T, ua, ud, tau=0.0, lam=0, apply_updates=False)
-        bad_acc = valid & (r.accept_margin < TOL_ACCEPT) & (ua != 0)
-        bad_draw = np.zeros((B, k + 1), bool)
-        bad_draw[:, :k] = valid & r.rejected & (r.draw_margin[:, :k] < TOL_DRAW)
-        bad_draw[:, k] = r.draw_margin[:, k] < TOL_DRAW
-        if not bad_acc.any() and not bad_draw.any():
+        bad_acc = valid & (r.accept_margin < TOL_ACCEPT)
+        if not bad_acc.any():
             return ua, ud
-        if attempt >= tries - 2:
-            ua[bad_draw[:, :k]] = 0.0                       # give up on these residuals: accept the position
-            ua[bad_acc] = 0.0
-        else:
-            ua[bad_acc] = rng.random(int(bad_acc.sum()), dtype=np.float32)
-        ud[bad_draw] = rng.random(int(bad_draw.sum()), dtype=np.float32)
-    raise AssertionError("could not settle the random numbers of a step")
+        ua[bad_acc] = rng.random(int(bad_acc.sum()), dtype=np.float32)
+    raise AssertionError("could not settle the acceptance numbers of a step")
+
+
+def _draw_weights(zp, zq, b, i, k, T):
+    """The weights a draw inverts, from the oracle's own functions: the residual of position i < k, or p_{k+1}."""
+    p = OS.softmax_T(OS.widen(zp[b, i]), T)
+    if i == k:
+        return p
+    return np.maximum(0.0, p - OS.softmax_T(OS.widen(zq[b, i]), T))
+
+
+def _tokens_within_tolerance(w, u, tol):
+    """{token: a u' at the middle of its interval} for every token with mass whose interval of the running sum of
+    w comes within tol (probability mass, as the oracle's draw margin) of u * R: the draws correct at that tolerance."""
+    c = np.cumsum(w)
+    R = float(c[-1])
+    target = float(u) * R
+    lo = int(np.searchsorted(c, target - tol, side="right"))
+    hi = min(int(np.searchsorted(c, target + tol, side="right")), len(w) - 1)
+    out = {}
+    for v in range(max(lo - 1, 0), hi + 1):
+        if w[v] > 0.0 and c[v] - w[v] <= target + tol and c[v] >= target - tol:
+            out[v] = (float(c[v]) - 0.5 * float(w[v])) / R
+    return out
+
+
+class DrawStats:
+    """How many draws of a run sat within TOL_DRAW of a boundary, and how many of those the GPU resolved the other way."""
+    def __init__(self):
+        self.draws = self.near_boundary = self.other_neighbour = 0
+
+
+def check_sampled_step(orc, zp, zq, draft, T, ua, ud, tau, lam, bf, where="", stats=None, apply_updates=True):
+    """Run the oracle on the step, compare every output of the GPU with it, and apply the step's updates to the
+    oracle's memory.  A draw whose u * R lies within TOL_DRAW of a boundary of the running sum has two correct
+    outcomes (csd.h says so).  For such a draw the GPU's token must be one of the tokens whose interval - by the
+    oracle's running sum - comes within the tolerance; if it is not the oracle's own, the oracle is run again on
+    that sequence with the draw moved to the middle of that token's interval, and everything downstream (gate,
+    lookup, accept length, emitted token, log, memory) is compared on that branch.  No case is dropped."""
+    B, K1, V = zp.shape
+    k = K1 - 1
+    view = O.CSDOracle(capacity=orc.capacity)        # same table, own counters: sequences may be run twice
+    view.T = orc.T
+    res = OS.verify_step_sampled(view, zp, zq, draft, T, ua, ud, tau=tau, lam=lam, apply_updates=False)
+    g_tstar, g_bonus = bf.tstar.cpu().numpy(), bf.bonus_token.cpu().numpy()
+    valid = (draft >= 0) & (draft < V)
+    drawn = np.zeros((B, K1), bool)
+    drawn[:, :k] = res.rejected & valid
+    drawn[:, k] = True
+    near = drawn & (res.draw_margin < TOL_DRAW)
+    if stats is not None:
+        stats.draws += int(drawn.sum())
+        stats.near_boundary += int(near.sum())
+    for b in np.nonzero(near.any(axis=1))[0]:
+        ud_b = ud[b].astype(np.float64)
+        moved = False
+        for i in np.nonzero(near[b])[0]:
+            mine = int(res.tstar[b, i]) if i < k else int(res.bonus_token[b])
+            theirs = int(g_tstar[b, i]) if i < k else int(g_bonus[b])
+            if theirs == mine:
+                continue
+            ok = _tokens_within_tolerance(_draw_weights(zp, zq, b, i, k, T), ud[b, i], TOL_DRAW)
+            assert theirs in ok, "%s sequence %d draw %d: token %d is not within %g of mass of u*R (oracle %d, valid %r)" % (
+                where, b, i, theirs, TOL_DRAW, mine, sorted(ok))
+            ud_b[i] = ok[theirs]
+            moved = True
+            if stats is not None:
+                stats.other_neighbour += 1
+        if moved:
+            rb = OS.verify_step_sampled(view, zp[b:b + 1], zq[b:b + 1], draft[b:b + 1], T, ua[b:b + 1], ud_b[None], tau=tau,
+                                        lam=lam, apply_updates=False)
+            res.rescued += rb.rescued - sum(1 for i in range(k) if (res.flags[b, i] & O.FLAG_COUNTED) and (res.flags[b, i] & O.FLAG_ACCEPTED))
+            for name in ("accept_len", "next_token", "alpha", "p_draft", "q_draft", "rejected", "tstar", "ratio", "bonus_token",
+                         "flags"):
+                getattr(res, name)[b] = getattr(rb, name)[0]
+            res.log[b] = rb.log[0]
+    compare_sampled_step(res, bf, where)
+    # what the loop of each sequence ended on: an id outside the vocabulary is counted once per sequence that reached it
+    for b in range(B):
+        n = int(res.accept_len[b])
+        if n < k and not valid[b, n]:
+            orc.bad_draft += 1
+    if apply_updates:
+        for pending in res.log:
+            orc.ocm_update(pending)
+    return res
 
 
 def compare_sampled_step(res, bf, where: str = ""):
@@ -176,15 +252,15 @@ def run_sampled_stream(workload, steps, T, tau=None, lam=None, capacity=None, pr
         csd.csd_ocm_update(ocm, keys, torch.tensor(weights, dtype=torch.int32, device="cuda"))
     bf = None
     rescued = counted = rejected = 0
+    stats = DrawStats()
     for step in steps:
         zp, zq, draft, ua, ud = workload.sampled_step(step, threads=threads)
         ua, ud = settle_uniforms(zp, zq, draft, T, ua, ud, seed=step)
         bf = csd.csd_verify_sampled(to_device_logits(zp), to_device_logits(zq), torch.from_numpy(draft).cuda(), T,
                                     torch.from_numpy(ua).cuda(), torch.from_numpy(ud).cuda(), tau, lam, ocm, buffers=bf)
         torch.cuda.synchronize()
-        res = OS.verify_step_sampled(orc, zp, zq, draft, T, ua, ud, tau=np.float32(tau), lam=lam)
         where = "%s T=%g step %d" % (cfg.name, T, step)
-        compare_sampled_step(res, bf, where)
+        res = check_sampled_step(orc, zp, zq, draft, T, ua, ud, np.float32(tau), lam, bf, where, stats)
         rescued += res.rescued
         counted += sum(len(l) for l in res.log)
         rejected += int(res.rejected.sum())
@@ -196,4 +272,6 @@ def run_sampled_stream(workload, steps, T, tau=None, lam=None, capacity=None, pr
     compare_table(ocm, orc, cfg.name + " final")
     st = bf.status.cpu().numpy().view(np.uint32)
     assert st[csd.CSD_STATUS_RESCUED] == rescued and st[csd.CSD_STATUS_COUNTED] == counted
+    print("%s T=%g: %d draws, %d within %g of a boundary, %d of those resolved to the other neighbour" % (
+        cfg.name, T, stats.draws, stats.near_boundary, TOL_DRAW, stats.other_neighbour))
     return orc, ocm, rescued, counted, rejected

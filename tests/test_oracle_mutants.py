@@ -134,6 +134,14 @@ MUTANTS_SAMPLED = [
     ("rescue_needs_only_gate", "if is_freq and is_safe:", "if is_safe:"),
     ("keeps_going_after_stop", "                res.next_token[b] = ts\n                stopped = True\n                break",
      "                res.next_token[b] = ts\n                stopped = True\n                continue"),
+    ("invalid_id_emits_the_bonus_draw", "                res.next_token[b] = int(np.argmax(widen(zp[b, i])))\n                stopped = True\n",
+     "                res.next_token[b] = int(np.argmax(widen(zp[b, i])))\n                stopped = False\n"),
+    ("invalid_id_emits_argmax_of_the_wrong_row", "res.next_token[b] = int(np.argmax(widen(zp[b, i])))",
+     "res.next_token[b] = int(np.argmax(widen(zp[b, 0])))"),
+    ("invalid_id_is_skipped_not_a_stop", "                res.next_token[b] = int(np.argmax(widen(zp[b, i])))\n                stopped = True\n                break",
+     "                res.next_token[b] = int(np.argmax(widen(zp[b, i])))\n                stopped = True\n                continue"),
+    ("empty_residual_reports_token_zero", "                t = int(np.argmax(z))                 # no residual mass: the target's own choice",
+     "                t = 0"),
 ]
 
 SAMPLED_PINS = [
@@ -146,6 +154,8 @@ SAMPLED_PINS = [
     sampled_pins.test_gate_uses_raw_logits_whatever_the_temperature,
     sampled_pins.test_counts_equal_bruteforce_recount_and_snapshot_rule,
     sampled_pins.test_equal_models_accept_everything,
+    sampled_pins.test_invalid_draft_id_ends_the_loop_uncounted,
+    sampled_pins.test_residual_without_mass_reports_the_target_argmax,
 ]
 
 

@@ -197,8 +197,52 @@ def test_counts_equal_bruteforce_recount_and_snapshot_rule():
     for d in range(V):
         for t in range(V):
             assert orc.T.get((d, t), 0) == dense[d, t]
-    assert rescued == 0 or rescued > 0
+    assert rescued > 0                                            # pairs recur on 8 tokens: some cross the threshold
     assert sum(orc.T.values()) == dense.sum() > 100
+
+
+def test_invalid_draft_id_ends_the_loop_uncounted():
+    """Hand-stated: V = 4, k = 3.  Position 0 is accepted (r = 0); position 1 carries an id outside the
+    vocabulary (4, then -1): the loop ends there, nothing is counted, nothing is looked up, the emitted token is
+    the argmax of that position's target row, and position 2 is never processed - although its own acceptance
+    test and draw are still reported.  The memory and the rescue counter are untouched; bad_draft counts one."""
+    zp = np.array([[[3.0, 0.0, 0.0, 0.0], [0.0, 0.0, 5.0, 0.0], [0.0, 4.0, 0.0, 0.0], [1.0, 0.0, 0.0, 0.0]]], np.float32)
+    zq = np.array([[[3.0, 0.0, 0.0, 0.0], [0.0, 0.0, 0.0, 0.0], [0.0, 0.0, 0.0, 6.0]]], np.float32)
+    for bad in (4, -1, 2 ** 31 - 1):
+        orc = O.CSDOracle()
+        orc.ocm_update([(3, 1)], [9])
+        draft = np.array([[0, bad, 3]], np.int32)
+        r = OS.verify_step_sampled(orc, zp, zq, draft, 1.0, np.array([[0.0, 0.0, 0.999]]), np.array([[0.5, 0.5, 0.5, 0.5]]),
+                                   tau=0.0, lam=0)
+        assert r.accept_len.tolist() == [1] and r.next_token.tolist() == [2]        # argmax of target row 1
+        assert r.flags[0].tolist() == [O.FLAG_MATCH | O.FLAG_ACCEPTED, 0, 0]
+        assert r.log == [[]] and r.rescued == 0 and orc.T == {(3, 1): 9} and orc.bad_draft == 1
+        assert bool(r.rejected[0, 1]) and int(r.tstar[0, 1]) == -1 and r.alpha[0, 1] == 0.0 and r.ratio[0, 1] == 0.0
+        # position 2 (never reached): q puts its mass on token 3, p on token 1 -> rejected, residual on token 1
+        assert bool(r.rejected[0, 2]) and int(r.tstar[0, 2]) == 1
+    # the same id behind a stop is never reached, hence not counted as bad: at position 0 the draft model is sure
+    # of token 3 (q = 0.99) which the target gives 0.04, so r = 0.999 rejects; the residual's mass sits on token 0
+    # (0.87 of 0.95), u = 0.5 draws it; the gate ratio e^-3 is below tau = 0.9: not rescued, the loop stops
+    zq2 = zq.copy()
+    zq2[0, 0] = [0.0, 0.0, 0.0, 6.0]
+    orc = O.CSDOracle()
+    r = OS.verify_step_sampled(orc, zp, zq2, np.array([[3, 4, 0]], np.int32), 1.0, np.array([[0.999, 0.0, 0.0]]),
+                               np.array([[0.5, 0.5, 0.5, 0.5]]), tau=0.9, lam=0)
+    assert r.accept_len.tolist() == [0] and r.next_token.tolist() == [0] and orc.bad_draft == 0 and r.log == [[(3, 0)]]
+    assert r.ratio[0, 0] == pytest.approx(np.exp(-3.0), rel=1e-12) and orc.T == {(3, 0): 1}
+
+
+def test_residual_without_mass_reports_the_target_argmax():
+    """p == q leaves max(0, p - q) without any mass.  With r in [0, 1] that case is never drawn from (alpha = 1
+    accepts); an r above 1 - outside the interface's range, used here only to reach the branch - shows what it
+    reports: the target row's lowest-id argmax, with a gate ratio of exp(z(draft) - z(argmax))."""
+    zp = np.array([[[1.0, 4.0, 4.0, 0.0], [0.0, 0.0, 0.0, 2.0]]], np.float32)
+    r = OS.verify_step_sampled(O.CSDOracle(), zp, zp[:, :1].copy(), np.array([[0]], np.int32), 0.7, np.array([[1.5]]),
+                               np.array([[0.3, 0.3]]), tau=0.01, lam=0)
+    assert bool(r.rejected[0, 0]) and r.alpha[0, 0] == 1.0 and r.res_mass[0, 0] == 0.0
+    assert int(r.tstar[0, 0]) == 1                                  # tokens 1 and 2 tie: the lower id
+    assert r.ratio[0, 0] == pytest.approx(np.exp(-3.0), rel=1e-12)
+    assert r.log == [[(0, 1)]] and r.accept_len.tolist() == [1]     # e^-3 >= 0.01 and lambda = 0: rescued
 
 
 def test_equal_models_accept_everything():
