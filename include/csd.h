@@ -258,8 +258,9 @@ int csd_ocm_export(const uint64_t *ocm, uint64_t capacity, uint64_t *keys_out, u
 
 /*
  * Row partials: the streaming pass over the logits on its own (the p_{1:gamma+1}(.) statistics of
- * Algorithm 1 before any verification logic).  A row's tiles are dealt to several waves; each
- * leaves one csd_row_partial for its share (an interleaved subset of the row, not a contiguous range).  A row's statistics follow from its partials as
+ * Algorithm 1 before any verification logic).  A row is cut into shares, one per wave (a wave's share is a
+ * strided subset of a run of 32 KiB tiles, not a contiguous range of tokens); each wave leaves one
+ * csd_row_partial for its share.  A row's statistics follow from its partials as
  *     m  = max_j m_j
  *     t* = min{ idx_j : m_j == m }                       (float comparison)
  *     S  = sum_j s_j * 2^(cref_j - m * CSD_LOG2E_F32)    (skip partials with s_j == 0)

@@ -109,7 +109,7 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     a.sharded = 0;
     a.n_shards = 1;
     a.shard_partials[0] = nullptr;                        // the records of the single-launch step take their place
-    a.shard_per_row[0] = plan.partials_per_row;
+    a.shard_per_row[0] = plan.nsplit;                     // one record per streaming workgroup
     a.shard_base[0] = 0;
     a.draft_logit = nullptr;
     a.accept_len = accept_len;

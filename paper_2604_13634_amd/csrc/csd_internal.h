@@ -19,8 +19,8 @@ constexpr int kStreamUnroll = 8;             // 16-byte loads in flight per lane
 constexpr int kTileChunks = kStreamWaves * kWaveSize * kStreamUnroll;   // 16-byte chunks per workgroup iteration (32 KiB)
 
 // Launch plan of the streaming pass; a pure function of the shape so that the workspace size query and
-// the launch agree.  A row's whole tiles are dealt round-robin to `nsplit` workgroups; the workgroup
-// (ntiles_row % nsplit) also takes the remainder (chunks past the last whole tile, ragged one included).
+// the launch agree.  A row's whole tiles are cut into `nsplit` contiguous runs, one per workgroup; the last
+// workgroup also takes the remainder (chunks past the last whole tile, ragged one included).
 struct StreamPlan {
     int rows;              // verify rows, B * (k + 1)
     int elems_per_chunk;   // 4 (fp32) or 8 (bf16) logits per 16-byte chunk
@@ -32,8 +32,8 @@ struct StreamPlan {
 
 StreamPlan make_stream_plan(int rows, int V, int dtype);
 
-// What a streaming wave of the single-launch step hands to the sequence waves of the same launch: its row
-// partial (w0 = m | cref << 32, w1 = s | idx << 32) and a check word, a 64-bit hash of the two data words, of a
+// What a streaming workgroup of the single-launch step hands to the sequence waves of the same launch: the row
+// partial of its four waves together (w0 = m | cref << 32, w1 = s | idx << 32) and a check word, a 64-bit hash of the two data words, of a
 // per-call number and of the record's index.  A reader takes a record as written once the check holds (a torn
 // read fails it); arbitrary memory passes with probability 2^-64, so the workspace needs no initialisation.
 // Readers zero the check word after use: a replay of the same call (a captured graph carries the same per-call
@@ -56,7 +56,7 @@ constexpr uint64_t kStepMagic = 0x3153444e56445343ull;
 // csd_verify workspace: [control | records | rejection log].  Nothing but the control head outlives a call.
 struct WorkspaceLayout {
     size_t ticket_off;                       // the control head (the ticket of the two-launch forms lives here too)
-    size_t partials_off, partials_bytes;     // StepRecord per streaming wave
+    size_t partials_off, partials_bytes;     // StepRecord per streaming workgroup
     size_t log_off, log_bytes;
     size_t total;
 };
@@ -94,7 +94,7 @@ struct EpilogueArgs {
     uint32_t *batch_ticket;  // [2]: the ticket, and a spare counter; zero when the finish kernel starts
     int apply_updates;
     // single-launch step only
-    StepRecord *records;     // [rows][partials_per_row]
+    StepRecord *records;     // [rows][nsplit]: one per streaming workgroup
     StepControl *ctrl;
     uint64_t nonce;          // per-call number behind the records' tags
     int n_stream_wgs;        // workgroups [0, n_stream_wgs) stream rows, the rest take sequences

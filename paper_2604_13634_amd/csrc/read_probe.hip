@@ -1,5 +1,5 @@
 // Read-only bandwidth probe with the load shape of the streaming pass: workgroups of 4 waves, 8 non-temporal
-// 16-byte loads in flight per lane, a row's 32 KiB tiles dealt round-robin to `nsplit` workgroups.  It does no
+// 16-byte loads in flight per lane, a row's 32 KiB tiles cut into `nsplit` contiguous runs, one per workgroup.  It does no
 // arithmetic beyond OR-ing the loaded words together (so that the loads cannot be dropped), which makes its
 // rate the ceiling of this access pattern on this machine.  Benchmark support only: it is not part of the
 // verification library and csd.h does not declare it.
@@ -14,16 +14,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(kWaves *kLanes, 4) void read_probe_kernel(const char *base, int64_t pitch, int64_t chunks_per_row,
                                                                       int nsplit, uint32_t *sink) {
     const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
-    const int64_t ntiles = chunks_per_row / kTileChunks;
-    const u32x4 *p = (const u32x4 *)(base + (int64_t)row * pitch) + (int64_t)split * kTileChunks + threadIdx.x;
+    const int64_t ntiles_row = chunks_per_row / kTileChunks;
+    const int64_t base_tiles = ntiles_row / nsplit, extra = ntiles_row - base_tiles * nsplit;
+    const int64_t tile0 = split * base_tiles + (split < extra ? split : extra);
+    const int64_t ntiles = base_tiles + (split < extra ? 1 : 0);
+    const u32x4 *p = (const u32x4 *)(base + (int64_t)row * pitch) + tile0 * kTileChunks + threadIdx.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
-    for (int64_t t = split; t < ntiles; t += nsplit) {
+    for (int64_t t = 0; t < ntiles; ++t) {
         u32x4 q[kLoads];
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) q[u] = __builtin_nontemporal_load(p + u * (kWaves * kLanes));
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) acc |= q[u];
-        p += (int64_t)nsplit * kTileChunks;
+        p += kTileChunks;
     }
     const uint32_t v = acc.x | acc.y | acc.z | acc.w;
     if (v == 0x9E3779B9u) sink[0] = v;                    // practically never: the store only keeps `acc` alive
