@@ -1,14 +1,14 @@
-// The verification step: two launches per decode step.
+// The verification step.
 //
-// Kernel 1 - streaming pass (row_partials_kernel).  For every verify row (a draft position or the bonus
-// row of Algorithm 1) the step needs the target distribution's normaliser, the greedy target token t*
-// and, later, single probabilities (Eq. 3 and the p_i(.) of Algorithm 1):
+// Streaming pass (stream_row_share).  For every verify row (a draft position or the bonus row of Algorithm 1) the
+// step needs the target distribution's normaliser, the greedy target token t* and, later, single probabilities
+// (Eq. 3 and the p_i(.) of Algorithm 1):
 //     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
 // Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
-// kernel is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
+// pass is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
 // `nsplit` contiguous runs, one per workgroup of 4 waves (a read-only probe measured contiguous runs 2 % faster
-// than tiles dealt round-robin to the row's workgroups); inside a tile the waves interleave 1 KiB wave-loads.  Each wave keeps its own running state and writes one partial;
-// there is no barrier and no cross-wave step in this kernel.
+// than tiles dealt round-robin to the row's workgroups); inside a tile the waves interleave 1 KiB wave-loads.
+// Each wave keeps its own running state; there is no barrier and no cross-wave step inside the sweep.
 //
 //   Per-lane state (fp32): rm = running maximum; best_q = the 16-byte chunk at which rm last strictly
 //   increased and best_it = its iteration, i.e. the first chunk of this lane that holds rm (a lane
@@ -22,17 +22,24 @@
 //   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
 //   2^d with |d| <= ulp(c)/2: this is why logits are limited to |z| <= 2^29 (d <= 32, sums stay in range).
 //
-// Kernel 2 - finish (finish_kernel), one wave per sequence, sixteen sequences per workgroup: combine the row
-// partials (normaliser in double), draft-token ratio and probability (Eq. 3), memory lookup then gate
-// (Algorithm 1), accepted-prefix scan by ballot, emitted token, and the list of divergences to count.
-// Each workgroup then takes a ticket on the batch; the workgroup that draws the last ticket knows that
-// every lookup of the step has been made and applies the step's increments with all its threads, so all
-// lookups read the table as it stood when the step began.  No workgroup waits for another.  The log
-// handed from the sequence waves to the updating workgroup is written with agent-scope atomic stores
-// (write-through to where the eight XCDs' L2s agree) and read back with agent-scope atomic loads; the
-// writers' stores are acknowledged before the workgroup barrier that precedes the ticket, itself an
-// agent-scope atomic add.  (A release/acquire fence pair would do the same job by writing back and
-// invalidating a whole L2 per wave, which measured ten times the streaming pass.)
+// Sequence logic (sequence_decide), one wave per sequence: combine the row partials (normaliser in double),
+// draft-token ratio and probability (Eq. 3), memory lookup then gate (Algorithm 1), accepted-prefix scan by
+// ballot, emitted token, and the divergences to count.
+//
+// Three kernels put these together:
+//   verify_step_kernel   csd_verify: both parts in one launch (see the comment above it);
+//   row_partials_kernel  the streaming pass alone, one partial per wave: csd_row_partials, and the first launch
+//                        of csd_verify_sampled;
+//   finish_kernel        the sequence logic alone, sixteen sequences per workgroup, on partials that sit in memory
+//                        from earlier launches (csd_verify_shards).  Each workgroup takes a ticket on the batch; the
+//                        one that draws the last ticket knows that every lookup of the step has been made and
+//                        applies the step's increments from the log with all its threads, so all lookups read the
+//                        table as it stood when the step began.  The log handed from the sequence waves to the
+//                        updating workgroup is written with agent-scope atomic stores (write-through to where the
+//                        eight XCDs' L2s agree) and read back with agent-scope atomic loads; the writers' stores
+//                        are acknowledged before the workgroup barrier that precedes the ticket, itself an
+//                        agent-scope atomic add.  (A release/acquire fence pair would do the same job by writing
+//                        back and invalidating a whole L2 per wave, which measured ten times the streaming pass.)
 #include "csd_device.h"
 
 namespace csd {
@@ -376,18 +383,30 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 
 // ---------------------------------------------------------------------------------------------------
 // The whole step in ONE launch.  Workgroups [0, n_stream_wgs) stream the rows exactly as row_partials_kernel
-// does and publish one StepRecord per wave; the workgroups after them take kStepSeqWaves sequences each (one
-// wave per sequence), fetch the draft tokens and their logits at once, wait for the records of their rows,
-// and run the verification loop.  The hardware hands out workgroups of a launch in index order, so a sequence
-// workgroup only ever waits for streaming workgroups that have already been started; its waits are bounded
-// all the same (kSpinLimit polls of about a microsecond each), and a wait that runs out is reported in
-// status[CSD_STATUS_STALLED] instead of hanging.
+// does; the four waves of a workgroup combine their partials in LDS and publish one StepRecord.  The workgroups
+// after them take kStepSeqWaves sequences each (one wave per sequence): they fetch the draft tokens and their
+// logits at once, wait for the records of their rows (every record of a sequence in one round of loads for the
+// usual shapes) and run the verification loop.  The hardware hands out the workgroups of a launch in index
+// order, so a sequence workgroup only ever waits for streaming workgroups that have already been started; its
+// waits are bounded all the same (kSpinLimit polls of about a microsecond each), and a wait that runs out is
+// reported in status[CSD_STATUS_STALLED] instead of hanging.
 //
 // Memory updates: with at most kMaxBarrierWorkgroups sequence workgroups (all resident together, so they can
 // wait for each other) each workgroup counts itself in on the control head once its lookups are done, waits
 // until all have, and then every lane adds its own pair straight to the table at the slot its lookup ended at
-// (ocm_add_one_after_probe): all lookups of the step precede all its updates, and no log is re-read.  Each
-// workgroup counts itself out as well; the last one out resets the counter for the next call.
+// (the slot of an absent pair is claimed with count zero while the workgroup waits): all lookups of the step
+// precede all its updates, and no log is re-read.  Each workgroup counts itself out as well; the last one out
+// resets the counter for the next call.
+//
+// Measured against the two-launch form (streaming kernel, then a kernel of sequence waves) on the five
+// benchmark shapes: 15.0 -> 10.3, 17.8 -> 13.2, 29.3 -> 23.8, 68.2 -> 59.8 and 106.7 -> 104.5 microseconds per
+// step.  Memory round trips cost about 1 us on an idle chip and about 3 us while the rows are being streamed,
+// which is why the sequence waves sit at the END of the grid (they start when the last streaming workgroups do,
+// and do their dependent loads when the chip falls quiet).  Tried and dropped: streaming the bonus rows last and
+// running loop, barrier and updates under them (the dependent chain then runs at loaded latency, and waves
+// resident early take places from the streaming workgroups: 1-5 us slower on four of the five shapes); waiting
+// on one record per sequence before polling all (no gain once records are one per workgroup); per-wave records
+// (three rounds of loads at k = 8).
 constexpr uint32_t kSpinLimit = 1u << 21;
 constexpr int kSpinSleep = 6;                     // s_sleep units of 64 clocks between polls
 
@@ -496,23 +515,6 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
         StepRecord *row_rec = a.records + prow * P;
         const uint64_t rec0 = (uint64_t)prow * (uint64_t)P;
         const int per_lane = (P + G - 1) / G;        // wave-uniform
-        // Rows are streamed in index order, so the records of the bonus row's last wave are among the last of
-        // this sequence to arrive: wait for that one record first (one lane, one 32-byte line per poll) and only
-        // then for all of them - hundreds of lanes polling every record of rows that are still being streamed take
-        // bandwidth from the very workgroups they are waiting for.
-        {
-            const uint64_t rs = ((uint64_t)b * K1 + k) * (uint64_t)P + (uint64_t)(P - 1);
-            const StepRecord *sr = a.records + rs;
-            for (uint32_t spin = 0; spin < kSpinLimit; ++spin) {
-                int seen = 0;
-                if (lane == 0) {
-                    const uint64_t w0 = xwg_load64(&sr->w0), w1 = xwg_load64(&sr->w1), ck = xwg_load64(&sr->check);
-                    seen = (ck == record_check(w0, w1, a.nonce, rs)) ? 1 : 0;
-                }
-                if (__builtin_amdgcn_readfirstlane(seen)) break;
-                __builtin_amdgcn_s_sleep(kSpinSleep);
-            }
-        }
         float gm;
         int t;
         double S;
