@@ -87,8 +87,8 @@ extern "C" {
 #define CSD_POS_COUNTED 16u  /* pair handed to UpdateMemory                         */
 
 /*
- * Bytes of device scratch csd_verify needs for this shape (per-wave row partials, the step's
- * rejection log and a completion ticket).  Returns 0 for invalid arguments.  Host function, no GPU work.
+ * Bytes of device scratch csd_verify needs for this shape (one record per streaming workgroup, the step's
+ * rejection log and a small control head).  Returns 0 for invalid arguments.  Host function, no GPU work.
  */
 size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
 
@@ -129,13 +129,15 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  *   rej_log     [B][k]    CSD_OCM_KEY(draft, t*) for each counted divergence, CSD_OCM_EMPTY elsewhere
  *                         (nullable; with flags == 0 it can be replayed later through csd_ocm_update).
  *   status      [CSD_STATUS_WORDS] counters, incremented (nullable).
- * A step is two kernel launches: the streaming pass over the logits, then one wave per sequence for
- * the verification logic; the workgroup that completes the batch applies the updates (batches of more than
- * 8192 draft positions use a third launch for them).
+ * A step is ONE kernel launch: workgroups that stream the logits, followed in the same grid by one wave per
+ * sequence for the verification logic, which waits for its rows' statistics and then applies the updates
+ * (batches of more than 256 sequences use a second launch for the updates).  Waits inside the launch are
+ * bounded: see CSD_STATUS_STALLED.
  * Scratch
  *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; needs no
- *                         initialisation, contents are undefined afterwards.  Two calls in flight must not
- *                         share a workspace.
+ *                         initialisation (any content will do the first time; the library keeps a few words of
+ *                         state in it between calls, so do not write to it in between).  Two calls in flight
+ *                         must not share a workspace.
  * B == 0 is a valid no-op.  k == 0 verifies nothing and returns the argmax of the single row.
  */
 int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,

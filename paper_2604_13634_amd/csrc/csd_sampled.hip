@@ -193,8 +193,12 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
     using C = Chunk<DT>;
     const int groups = (a.nseg + kSegBlockWaves * kSegsPerWave - 1) / (kSegBlockWaves * kSegsPerWave);
     const unsigned int items = *a.work_count * (unsigned int)groups;
+    // the row of the NEXT item is fetched while this one is streamed: otherwise every item would begin with a
+    // dependent load (three microseconds on a busy chip) before its own loads could be issued
+    int j_next = (blockIdx.x < items) ? a.work_rows[blockIdx.x / groups] : 0;
     for (unsigned int item = blockIdx.x; item < items; item += gridDim.x) {
-        const int j = a.work_rows[item / groups];
+        const int j = j_next;
+        if (item + gridDim.x < items) j_next = a.work_rows[(item + gridDim.x) / groups];
         const int group = (int)(item % groups);
         const DrawRow r = a.rows[j];
         const int lane = threadIdx.x & (kWaveSize - 1);

@@ -47,7 +47,7 @@ def test_full_size_steps_with_prior(ci, steps):
     assert rescued > 0
 
 
-@pytest.mark.parametrize("ci,steps", [(1, 400), (2, 150), (3, 80), (4, 80)])
+@pytest.mark.parametrize("ci,steps", [(1, 600), (2, 250), (3, 120), (4, 100)])
 def test_full_size_streams_from_an_empty_memory(ci, steps):
     """Configs 1-4 at full size (the shapes and launch configuration bench.py times), the memory evolving
     from empty: pairs cross the frequency threshold and are rescued without any prior.  Every step is
