@@ -6,8 +6,8 @@
 //     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
 // Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
 // pass is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
-// `nsplit` contiguous runs, one per workgroup of 4 waves (a read-only probe measured contiguous runs 2 % faster
-// than tiles dealt round-robin to the row's workgroups); inside a tile the waves interleave 1 KiB wave-loads.
+// `nsplit` contiguous runs, one per workgroup of 4 waves (dealing the tiles round-robin to the row's workgroups
+// instead measures the same); inside a tile the waves interleave 1 KiB wave-loads.
 // Each wave keeps its own running state; there is no barrier and no cross-wave step inside the sweep.
 //
 //   Per-lane state (fp32): rm = running maximum; best_q = the 16-byte chunk at which rm last strictly
