@@ -271,7 +271,8 @@ static SampledWorkspace sampled_layout(const StreamPlan &plan, int B, int k, int
     w.state_off = up(w.zpd_off + (size_t)B * k * sizeof(float));
     w.tstar_off = up(w.state_off + (size_t)B * k);
     w.bonus_off = up(w.tstar_off + (size_t)B * k * sizeof(int32_t));
-    w.log_off = up(w.bonus_off + (size_t)B * sizeof(int32_t));
+    w.draws_off = up(w.bonus_off + (size_t)B * sizeof(int32_t));
+    w.log_off = up(w.draws_off + (size_t)B * K1 * sizeof(WordRecord));
     w.total = up(w.log_off + (size_t)B * k * sizeof(uint64_t));
     return w;
 }
@@ -355,8 +356,15 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.rej_log = rej_log ? rej_log : (apply ? (uint64_t *)(wsp + ws.log_off) : nullptr);
     a.status = status;
     a.batch_ticket = (uint32_t *)(wsp + ws.ticket_off);
-    const bool update_in_finish = apply && (uint64_t)B * (uint64_t)k <= kMaxInKernelUpdates;
-    a.apply_updates = update_in_finish ? 1 : 0;
+    a.draws = (WordRecord *)(wsp + ws.draws_off);
+    a.ctrl = (StepControl *)(wsp + ws.ticket_off + 16);   // behind the two words the first launch zeroes
+    a.nonce = next_call_number();
+    a.n_loc_wgs = sampled_locate_workgroups(B, k);
+    // as in csd_verify: few sequence workgroups wait for each other and apply the updates themselves, many hand the
+    // log to the bulk update kernel
+    const bool update_in_finish = apply && sampled_sequence_workgroups(B) <= kMaxBarrierWorkgroups;
+    a.update_here = update_in_finish ? 1 : 0;
+    if (update_in_finish && !rej_log) a.rej_log = nullptr;   // nobody reads a log then
 
     const StreamSource src = {(const char *)target_logits, target_row_stride * (int64_t)esz, rows_p,
                               (const char *)draft_logits, draft_row_stride * (int64_t)esz, scale};

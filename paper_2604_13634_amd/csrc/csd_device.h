@@ -493,6 +493,112 @@ __device__ __forceinline__ void apply_step_log(uint64_t *ocm, uint64_t capacity,
     block_apply_list(ocm, capacity, status, lds, fetch, 0, 1, n);
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Waiting inside a launch: waves that wait for what other workgroups of the same launch publish.  Every wait is
+// bounded: kSpinLimit polls of about a microsecond each (a poll is a memory round trip plus a short sleep).
+constexpr uint32_t kSpinLimit = 1u << 21;
+constexpr int kSpinSleep = 6;                     // s_sleep units of 64 clocks between polls
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+// What a lane carries out of the verification loop for the update phase.
+struct Divergence {
+    bool counted;        // this position's pair goes to UpdateMemory
+    uint64_t key;
+    OcmProbe probe;      // where the lookup ended (only when probed)
+};
+
+
+// The end of a sequence workgroup's step, called by all its threads: the per-workgroup status counters leave
+// (all but the rare lost insert are known; their atomics need no answer and travel while the workgroup waits),
+// and - update_here - the step's increments are applied after a barrier of the launch's `total` sequence
+// workgroups: every lookup of the step before any update of the step.
+//   An absent pair's slot is claimed at once (count zero: no lookup of the step reads it differently); the
+//   compare-and-swap is in flight during the barrier.  This workgroup's lookups have returned when it counts itself
+//   in (their values were used by the caller); its stores may still be on their way, nobody waits for them.
+//   The counter in the control head must be zero when a launch begins; `magic` (read early by thread 0) says that
+//   it has been set up, by the first workgroup of this launch at the latest.  Each workgroup also counts itself
+//   out, off the updates' path: the one that brings the counter to 2 * total is the last to have read it, and
+//   leaves it at zero for the next call.
+__device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t magic, uint32_t total, bool update_here,
+                                                              uint64_t *ocm, uint64_t capacity, uint32_t *status,
+                                                              BlockCounters &counters, const Divergence &dv, int *verdict) {
+    barrier_lds_only();
+    if (status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
+        atomicAdd(&status[threadIdx.x], counters.v[threadIdx.x]);
+    if (!update_here) return;
+    OcmClaim claim = {CSD_OCM_EMPTY, false, false};
+    if (dv.counted) claim = ocm_claim_after_probe(ocm, dv.key, dv.probe);
+    if (threadIdx.x == 0) {
+        bool good = true;
+        for (uint32_t spin = 0; magic != kStepMagic; ++spin) {
+            if (spin >= kSpinLimit) { good = false; break; }
+            __builtin_amdgcn_s_sleep(kSpinSleep);
+            magic = xwg_load64(&ctrl->magic);
+        }
+        if (good) {
+            __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (uint32_t spin = 0;; ++spin) {
+                if (__hip_atomic_load(&ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
+                if (spin >= kSpinLimit) { good = false; break; }
+                __builtin_amdgcn_s_sleep(kSpinSleep);
+            }
+        }
+        if (!good && status != nullptr) atomicAdd(&status[CSD_STATUS_STALLED], 1u);
+        *verdict = good ? 1 : 0;
+    }
+    barrier_lds_only();
+    const bool passed = *verdict != 0;
+    if (passed && dv.counted) {
+        if (!ocm_add_one_after_claim(ocm, capacity, dv.key, dv.probe, claim) && status != nullptr)
+            atomicAdd(&status[CSD_STATUS_DROPPED], 1u);
+    }
+    if (threadIdx.x == 0 && passed) {
+        const uint32_t old = __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == 2u * total - 1u) __hip_atomic_store(&ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// The first workgroup of a launch whose sequence workgroups will use the barrier: the counter starts at zero,
+// and only then does the magic say so (called by one thread).
+__device__ __forceinline__ void step_control_setup(StepControl *ctrl) {
+    if (xwg_load64(&ctrl->magic) == kStepMagic) return;
+    __hip_atomic_store(&ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the zero is acknowledged before the magic leaves
+    xwg_store64(&ctrl->magic, kStepMagic);
+}
+
+// Published words (WordRecord): same rules as StepRecord - a reader takes one once the check holds and zeroes the
+// check after use; arbitrary memory passes with probability 2^-64.
+__device__ __forceinline__ uint64_t word_check(uint64_t value, uint64_t nonce, uint64_t rec) {
+    return mix64(value + mix64(nonce + rec * 0x9E3779B97F4A7C15ull)) | 1ull;
+}
+__device__ __forceinline__ void publish_word(WordRecord *r, uint64_t nonce, uint64_t rec, uint64_t value) {
+    xwg_store64(&r->value, value);
+    xwg_store64(&r->check, word_check(value, nonce, rec));
+}
+// polled by the calling lane until it passes (bounded); false when the wait ran out
+__device__ __forceinline__ bool acquire_word(WordRecord *r, uint64_t nonce, uint64_t rec, uint64_t &value) {
+    for (uint32_t spin = 0;; ++spin) {
+        value = xwg_load64(&r->value);
+        const uint64_t ck = xwg_load64(&r->check);
+        if (ck == word_check(value, nonce, rec)) {
+            xwg_store64(&r->check, 0ull);
+            return true;
+        }
+        if (spin >= kSpinLimit) return false;
+        __builtin_amdgcn_s_sleep(kSpinSleep);
+    }
+}
+
 __device__ __forceinline__ float load_logit(const void *logits, int dtype, int64_t elem) {
     if (dtype == CSD_DTYPE_F32) return ((const float *)logits)[elem];
     return __uint_as_float((uint32_t)((const uint16_t *)logits)[elem] << 16);

@@ -43,6 +43,12 @@ struct StepRecord {
 };
 static_assert(sizeof(StepRecord) == 32, "records are 32 bytes");
 
+// A published word: a 64-bit value with a check word beside it (a hash of the value, of a per-call number and of
+// the record's index).  What the draw waves of the sampled step's last launch hand to its sequence waves.
+struct WordRecord {
+    uint64_t value, check;
+};
+
 // Head of the csd_verify workspace.  `arrivals` is the counter behind the barrier of the sequence workgroups;
 // it is zero between calls (the last workgroup through resets it).  `magic` says that this has been set up:
 // the first workgroup of a launch that finds another value there zeroes the counter and writes the magic.
@@ -158,13 +164,20 @@ struct SampledArgs {
     uint8_t *pos_flags;
     uint64_t *rej_log;
     uint32_t *status;
-    uint32_t *batch_ticket;
-    int apply_updates;
+    uint32_t *batch_ticket;    // [2]: unused word, and the length of the list of rows to draw; zeroed by the first launch
+    WordRecord *draws;         // [B][k+1] the draws, published inside the last launch
+    StepControl *ctrl;         // barrier state of the last launch's sequence workgroups
+    uint64_t nonce;            // per-call number behind the draws' check words
+    int n_loc_wgs;             // workgroups of the last launch that invert running sums; the sequence workgroups follow
+    int update_here;           // 1: the sequence waves apply their own increments after a barrier among their workgroups
 };
 
 struct SampledWorkspace {
-    size_t ticket_off, partials_off, rows_off, work_off, segsum_off, zpd_off, state_off, tstar_off, bonus_off, log_off, total;
+    size_t ticket_off, partials_off, rows_off, work_off, segsum_off, zpd_off, state_off, tstar_off, bonus_off, draws_off, log_off,
+        total;
 };
+int sampled_locate_workgroups(int B, int k);
+int sampled_sequence_workgroups(int B);
 int sampled_segments(int V, int dtype);
 hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);
 

@@ -8,7 +8,7 @@
 //          count the pair, then keep x~ (rescued) or stop and emit t*
 //   all kept: emit a draw from p_{k+1}.
 //
-// Five launches on the caller's stream:
+// Four launches on the caller's stream:
 //   1. row_partials_kernel (csd_verify.hip) over the B(k+1) target rows and the Bk draft rows in one grid,
 //      with the exponent scale log2(e)/T: maxima and normalisers at temperature T.        [HBM-bound]
 //   2. sampled_decide_kernel, one wave per sequence: combine the partials, p(x~), q(x~), alpha, the
@@ -16,10 +16,11 @@
 //      that turn a logit into a probability, and a list of the rows that need a draw.
 //   3. residual_segments_kernel, a fixed grid walking that list: streams the target row and the draft row
 //      side by side and leaves the residual mass of every segment of 256 chunks.          [HBM-bound]
-//   4. residual_locate_kernel, one wave per draw row: scans the segment masses in double, finds the
-//      segment that holds u*R, re-reads that one segment and walks to the token.
-//   5. sampled_finish_kernel, one wave per sequence: lookup, gate, accepted-prefix scan, emitted token,
-//      log; the last workgroup applies the step's updates (same tail as the greedy path).
+//   4. sampled_tail_kernel.  First role, one wave per draw row: scans the segment masses in double, finds the
+//      segment that holds u*R, re-reads that one segment, walks to the token and publishes the draw.  Second
+//      role (workgroups at the end of the grid), one wave per sequence: waits for the draws of its rows, then
+//      lookup, gate, accepted-prefix scan, emitted token, log, and the step's updates after a barrier of the
+//      sequence workgroups (the same tail as the greedy step's single launch).
 // Positions whose acceptance test fails are all drawn (the draws do not depend on each other), although
 // the loop may stop before it reaches some of them; so is the bonus token of every sequence.
 #include "csd_device.h"
@@ -248,20 +249,18 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 4: invert the running sum.  One wave per draw row.
+// Launch 4, first role: invert the running sum.  One wave per draw row j; returns the drawn token (-1 when the
+// row needs no draw) in every lane and writes it to the tstar / bonus output.
 template <int DT>
-__global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledArgs a) {
+__device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int lane) {
     using C = Chunk<DT>;
-    const int lane = threadIdx.x & (kWaveSize - 1);
     const int K1 = a.k + 1;
-    const int64_t j = (int64_t)blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (j >= (int64_t)a.B * K1) return;
     const int b = (int)(j / K1), i = (int)(j - (int64_t)b * K1);
     int32_t *out = (i < a.k) ? &a.tstar[(int64_t)b * a.k + i] : &a.bonus[b];
     const DrawRow r = a.rows[j];
     if (!r.need) {
         if (lane == 0) *out = -1;
-        return;
+        return -1;
     }
     // ---- which segment: lane l owns segments [l*per, (l+1)*per)
     const float *seg = a.segsum + j * a.nseg;
@@ -350,33 +349,59 @@ __global__ __launch_bounds__(kApplyThreads) void residual_locate_kernel(SampledA
     }
     if (result < 0) result = r.fallback;                   // no residual mass at all: the target's own choice
     if (lane == 0) *out = result;
+    return result;
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 5: the loop itself.  One wave per sequence.
-__device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters) {
+// Launch 4, second role: the loop itself.  One wave per sequence; it waits for the draws of its k+1 rows, which
+// the first role's waves of the same launch publish.
+__device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters, bool &stalled) {
     const int k = a.k, K1 = a.k + 1;
     const bool is_pos = lane < k;
-    int d = -1, t = -1;
+    int d = -1;
     bool valid = false, rejected = false;
     float zpd = 0.f, zpt = 0.f;
-    if (is_pos) {
+    if (is_pos) {                                          // from the acceptance test's launch: there before this one began
         const int64_t o = (int64_t)b * k + lane;
         d = a.draft[o];
         const uint8_t st = a.pos_state[o];
         rejected = st & 1;
         valid = st & 2;
         zpd = a.pos_zpd[o];
-        t = a.tstar[o];
-        if (rejected && valid) zpt = load_logit(a.target, a.dtype, ((int64_t)b * K1 + lane) * a.target_stride + t);
     }
+    const int fallback = a.rows[(int64_t)b * K1 + (lane < K1 ? lane : 0)].fallback;
+    // the draws of this sequence's rows: lane i takes row i's
+    int t = -1;
+    bool got = true;
+    if (lane < K1) {
+        uint64_t v = 0;
+        const uint64_t rec = (uint64_t)b * K1 + lane;
+        got = acquire_word(a.draws + rec, a.nonce, rec, v);
+        t = (int)(uint32_t)v;
+    }
+    stalled = __builtin_amdgcn_ballot_w64(!got) != 0ull;
+    Divergence out;
+    out.counted = false;
+    out.key = 0;
+    out.probe = OcmProbe{0, 0, false, false};
+    if (stalled) return out;
+    const int bonus = from_lane_i(t, k);
+    if (is_pos && rejected && valid) zpt = load_logit(a.target, a.dtype, ((int64_t)b * K1 + lane) * a.target_stride + t);
+
     const bool diverges = is_pos && rejected && valid;
     // Eq. 3 on the raw target logits
     const double ratio = diverges ? exp2(((double)zpd - (double)zpt) * 1.4426950408889634) : 0.0;
     if (is_pos && a.ratio) a.ratio[(int64_t)b * k + lane] = (float)ratio;
-    const uint64_t key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? t : 0));
+    out.key = CSD_OCM_KEY((uint32_t)(diverges ? d : 0), (uint32_t)(diverges ? t : 0));
     bool is_freq = false;
-    if (diverges && a.ocm != nullptr) is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, key) >= a.lambda);
+    if (diverges && a.ocm != nullptr) {
+        if (a.update_here) {
+            out.probe = ocm_probe(a.ocm, a.capacity, out.key);
+            is_freq = out.probe.count >= a.lambda;
+        } else {
+            is_freq = (a.lambda == 0) ? true : (ocm_lookup(a.ocm, a.capacity, out.key) >= a.lambda);
+        }
+    }
     const bool is_safe = diverges && (ratio >= (double)a.tau);
     const bool ok = is_pos && (!rejected || (is_freq && is_safe));
 
@@ -384,9 +409,10 @@ __device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, in
     const int n = (int)__builtin_ctzll(fail);
     const bool processed = is_pos && (lane <= n);
     const bool counted = processed && diverges;
+    out.counted = counted;
     // emitted token: the stopping position's t* (the target argmax when its draft id was invalid), else the bonus draw
-    int mine = (diverges ? t : a.rows[(int64_t)b * K1 + (lane < K1 ? lane : 0)].fallback);
-    if (lane == k) mine = a.bonus[b];
+    int mine = diverges ? t : fallback;
+    if (lane == k) mine = bonus;
     const int next = from_lane_i(mine, n);
 
     if (is_pos) {
@@ -401,7 +427,7 @@ __device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, in
             }
             a.pos_flags[o] = f;
         }
-        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? key : CSD_OCM_EMPTY);
+        if (a.rej_log) xwg_store64(&a.rej_log[o], counted ? out.key : CSD_OCM_EMPTY);
     }
     const uint64_t m_counted = __builtin_amdgcn_ballot_w64(counted);
     const uint64_t m_rescued = __builtin_amdgcn_ballot_w64(counted && ok);
@@ -414,19 +440,49 @@ __device__ __forceinline__ void sampled_sequence(const SampledArgs &a, int b, in
         if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
         if (n) atomicAdd(&counters.v[CSD_STATUS_ACCEPTED], (unsigned int)n);
     }
+    return out;
 }
 
-__global__ __launch_bounds__(kApplyThreads) void sampled_finish_kernel(SampledArgs a) {
-    __shared__ ApplyLds lds;
+// Launch 4: workgroups [0, n_loc_wgs) invert the running sums (one wave per draw row) and publish each draw; the
+// workgroups after them take four sequences each, wait for their rows' draws and run the loop, then apply the
+// updates as the greedy step does (sequence_counters_and_updates).  Workgroups of a launch start in index order,
+// so a sequence wave only waits for waves that have been started.
+template <int DT>
+__global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel(SampledArgs a) {
     __shared__ BlockCounters counters;
     __shared__ int verdict;
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
+    const int wave = threadIdx.x >> 6;
+    const int K1 = a.k + 1;
+    if ((int)blockIdx.x < a.n_loc_wgs) {
+        if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl);
+        const int64_t j = (int64_t)blockIdx.x * kSegBlockWaves + wave;
+        if (j >= (int64_t)a.B * K1) return;
+        const int result = locate_draw<DT>(a, j, lane);
+        if (lane == 0) publish_word(a.draws + j, a.nonce, (uint64_t)j, (uint64_t)(uint32_t)result);
+        return;
+    }
+    const int wg = (int)blockIdx.x - a.n_loc_wgs;
+    const int n_seq_wgs = (int)gridDim.x - a.n_loc_wgs;
+    const int b = wg * kSegBlockWaves + wave;
+    uint64_t magic = 0;
+    if (a.update_here && threadIdx.x == 0) magic = xwg_load64(&a.ctrl->magic);
     block_counters_clear(counters);
-    if (b < a.B) sampled_sequence(a, b, lane, counters);
-    block_counters_flush(counters, a.status);
-    if (!a.apply_updates) return;
-    apply_step_log(a.ocm, a.capacity, a.status, a.rej_log, (uint64_t)a.B * (uint64_t)a.k, a.batch_ticket, lds, &verdict);
+    Divergence dv;
+    dv.counted = false;
+    dv.key = 0;
+    dv.probe = OcmProbe{0, 0, false, false};
+    if (b < a.B) {                                         // wave-uniform: a wave takes a sequence or none
+        bool stalled = false;
+        dv = sampled_sequence(a, b, lane, counters, stalled);
+        if (stalled && lane == 0) {                        // the draws never came: say so, and report nothing as accepted
+            a.accept_len[b] = 0;
+            a.next_token[b] = -1;
+            atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
+        }
+    }
+    sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
+                                  dv, &verdict);
 }
 
 }  // namespace
@@ -447,19 +503,20 @@ hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream) {
     const int per_block = kSegBlockWaves * kSegsPerWave;
     const int64_t max_items = (int64_t)a.B * K1 * ((a.nseg + per_block - 1) / per_block);
     const dim3 seg_grid((unsigned)(max_items < kSegGrid ? max_items : kSegGrid));
-    const dim3 row_grid((unsigned)(((int64_t)a.B * K1 + kFinishWaves - 1) / kFinishWaves));
+    const dim3 tail_grid((unsigned)(a.n_loc_wgs + (a.B + kSegBlockWaves - 1) / kSegBlockWaves)), tail_block(kSegBlockWaves * kWaveSize);
     if (a.dtype == CSD_DTYPE_F32) {
         hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(residual_locate_kernel<CSD_DTYPE_F32>, row_grid, seq_block, 0, stream, a);
+        hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_F32>, tail_grid, tail_block, 0, stream, a);
     } else {
         hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_BF16>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(residual_locate_kernel<CSD_DTYPE_BF16>, row_grid, seq_block, 0, stream, a);
+        hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_BF16>, tail_grid, tail_block, 0, stream, a);
     }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(sampled_finish_kernel, seq_grid, seq_block, 0, stream, a);
     return hipGetLastError();
 }
+
+int sampled_locate_workgroups(int B, int k) { return (int)(((int64_t)B * (k + 1) + kSegBlockWaves - 1) / kSegBlockWaves); }
+int sampled_sequence_workgroups(int B) { return (B + kSegBlockWaves - 1) / kSegBlockWaves; }
 
 }  // namespace csd

@@ -235,13 +235,6 @@ __device__ __forceinline__ void publish_row_stats(const EpilogueArgs &a, int b, 
     rS = from_lane_d(S, src);
 }
 
-// What a lane carries out of the verification loop for the update phase.
-struct Divergence {
-    bool counted;        // this position's pair goes to UpdateMemory
-    uint64_t key;
-    OcmProbe probe;      // where the lookup ended (only when probed)
-};
-
 // Algorithm 1 for one sequence, given its row statistics: ratio (Eq. 3), match, memory lookup, gate, accepted
 // prefix, emitted token, outputs and the per-workgroup status counters.  PROBE: keep where each lookup ended
 // (for updates applied straight from these lanes); the lookup is then made even when lambda == 0.
@@ -407,17 +400,6 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 // resident early take places from the streaming workgroups: 1-5 us slower on four of the five shapes); waiting
 // on one record per sequence before polling all (no gain once records are one per workgroup); per-wave records
 // (three rounds of loads at k = 8).
-constexpr uint32_t kSpinLimit = 1u << 21;
-constexpr int kSpinSleep = 6;                     // s_sleep units of 64 clocks between polls
-
-__device__ __forceinline__ uint64_t mix64(uint64_t x) {
-    x ^= x >> 30;
-    x *= 0xBF58476D1CE4E5B9ull;
-    x ^= x >> 27;
-    x *= 0x94D049BB133111EBull;
-    x ^= x >> 31;
-    return x;
-}
 // the check word of a record: a hash of its two data words, of the call's number and of the record's index
 __device__ __forceinline__ uint64_t record_check(uint64_t w0, uint64_t w1, uint64_t nonce, uint64_t rec) {
     return mix64(w0 + mix64(w1 ^ (nonce + rec * 0x9E3779B97F4A7C15ull))) | 1ull;   // never zero: a zeroed record does not pass
@@ -570,53 +552,8 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
         }
     }
 
-    // The step's counters leave now (all but the rare lost insert are known): their atomics need no answer
-    // and travel while the workgroup waits below.
-    barrier_lds_only();
-    if (a.status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
-        atomicAdd(&a.status[threadIdx.x], counters.v[threadIdx.x]);
-
-    if (a.update_here) {
-        // An absent pair's slot is claimed at once (count zero: no lookup of the step reads it differently); the
-        // compare-and-swap is in flight during the barrier below.
-        OcmClaim claim = {CSD_OCM_EMPTY, false, false};
-        if (dv.counted) claim = ocm_claim_after_probe(a.ocm, dv.key, dv.probe);
-        // ---- barrier among the sequence workgroups: every lookup of the step before any update of the step.
-        // This workgroup's lookups have returned (their values were used above); its stores may still be on their
-        // way, nobody waits for them.
-        if (threadIdx.x == 0) {
-            bool good = true;
-            for (uint32_t spin = 0; magic != kStepMagic; ++spin) {           // set up by workgroup 0 of this launch at the latest
-                if (spin >= kSpinLimit) { good = false; break; }
-                __builtin_amdgcn_s_sleep(kSpinSleep);
-                magic = xwg_load64(&a.ctrl->magic);
-            }
-            const uint32_t total = (uint32_t)n_seq_wgs;
-            if (good) {
-                __hip_atomic_fetch_add(&a.ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                for (uint32_t spin = 0;; ++spin) {
-                    if (__hip_atomic_load(&a.ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
-                    if (spin >= kSpinLimit) { good = false; break; }
-                    __builtin_amdgcn_s_sleep(kSpinSleep);
-                }
-            }
-            if (!good && a.status != nullptr) atomicAdd(&a.status[CSD_STATUS_STALLED], 1u);
-            *verdict = good ? (int)total : 0;
-        }
-        barrier_lds_only();
-        const int passed = *verdict;
-        if (passed != 0 && dv.counted) {
-            if (!ocm_add_one_after_claim(a.ocm, a.capacity, dv.key, dv.probe, claim) && a.status != nullptr)
-                atomicAdd(&a.status[CSD_STATUS_DROPPED], 1u);
-        }
-        if (threadIdx.x == 0 && passed != 0) {
-            // counted out, off the updates' path: the workgroup that brings the counter to 2 * total is the last to
-            // have read it, and leaves it at zero for the next call
-            const uint32_t total = (uint32_t)passed;
-            const uint32_t old = __hip_atomic_fetch_add(&a.ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (old == 2u * total - 1u) __hip_atomic_store(&a.ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+    sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
+                                  dv, verdict);
 }
 
 template <int DT>
@@ -633,12 +570,7 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void verify_step_kernel
     const int split = blockIdx.x - row * nsplit;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0 && xwg_load64(&a.ctrl->magic) != kStepMagic) {
-        // first use of this workspace: the counter starts at zero, and only then does the magic say so
-        __hip_atomic_store(&a.ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the zero is acknowledged before the magic leaves
-        xwg_store64(&a.ctrl->magic, kStepMagic);
-    }
+    if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl);
     const char *rowp = src.base0 + (int64_t)row * src.pitch0;
     const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
     // The four waves of the workgroup (they sweep the same tiles and end together) leave ONE record: fewer records
