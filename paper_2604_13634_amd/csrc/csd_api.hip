@@ -50,6 +50,12 @@ uint64_t next_call_number() {
     return counter.fetch_add(0x9E3779B97F4A7C15ull, std::memory_order_relaxed);
 }
 
+// Test hooks (csd_test_set_wait_rules, not part of csd.h): how long waits inside a launch may last, and a mask
+// that makes the readers' per-call number differ from the writers' so that nothing ever passes - the way to see,
+// without ever hanging a kernel, that a wait that runs out is reported and leaves everything consistent.
+std::atomic<uint32_t> g_spin_limit{1u << 21};
+std::atomic<uint64_t> g_reader_nonce_xor{0};
+
 constexpr int kMaxDevices = 64;
 std::atomic<void *> g_scratch_ptr[kMaxDevices];
 
@@ -134,6 +140,8 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     a.records = (StepRecord *)((char *)workspace + ws.partials_off);
     a.ctrl = (StepControl *)((char *)workspace + ws.ticket_off);
     a.nonce = next_call_number();
+    a.reader_nonce = a.nonce ^ g_reader_nonce_xor.load(std::memory_order_relaxed);
+    a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
     a.n_stream_wgs = plan.rows * plan.nsplit;
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, plan.rows, nullptr, 0, CSD_LOG2E_F32};
     if (launch_verify_step(src, dtype, V, plan, a, st) != hipSuccess) return CSD_EHIP;
@@ -359,6 +367,8 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.draws = (WordRecord *)(wsp + ws.draws_off);
     a.ctrl = (StepControl *)(wsp + ws.ticket_off + 16);   // behind the two words the first launch zeroes
     a.nonce = next_call_number();
+    a.reader_nonce = a.nonce ^ g_reader_nonce_xor.load(std::memory_order_relaxed);
+    a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
     a.n_loc_wgs = sampled_locate_workgroups(B, k);
     // as in csd_verify: few sequence workgroups wait for each other and apply the updates themselves, many hand the
     // log to the bulk update kernel
@@ -436,6 +446,13 @@ int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows
     if (partials_bytes < (size_t)rows * plan.partials_per_row * sizeof(RowPartial)) return CSD_ENOSPACE;
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, rows, nullptr, 0, CSD_LOG2E_F32};
     return launch_row_partials(src, dtype, V, plan, partials, nullptr, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+}
+
+// Test hook, deliberately absent from csd.h: spin_limit = polls a wait inside a launch may take (0 restores the
+// default), reader_nonce_xor != 0 makes every such wait run out.  Affects calls enqueued afterwards.
+void csd_test_set_wait_rules(uint32_t spin_limit, uint64_t reader_nonce_xor) {
+    g_spin_limit.store(spin_limit ? spin_limit : (1u << 21), std::memory_order_relaxed);
+    g_reader_nonce_xor.store(reader_nonce_xor, std::memory_order_relaxed);
 }
 
 const char *csd_strerror(int code) {

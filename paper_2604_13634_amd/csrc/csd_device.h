@@ -530,7 +530,8 @@ struct Divergence {
 //   leaves it at zero for the next call.
 __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t magic, uint32_t total, bool update_here,
                                                               uint64_t *ocm, uint64_t capacity, uint32_t *status,
-                                                              BlockCounters &counters, const Divergence &dv, int *verdict) {
+                                                              BlockCounters &counters, const Divergence &dv, int *verdict,
+                                                              uint32_t spin_limit) {
     barrier_lds_only();
     if (status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
         atomicAdd(&status[threadIdx.x], counters.v[threadIdx.x]);
@@ -540,7 +541,7 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
     if (threadIdx.x == 0) {
         bool good = true;
         for (uint32_t spin = 0; magic != kStepMagic; ++spin) {
-            if (spin >= kSpinLimit) { good = false; break; }
+            if (spin >= spin_limit) { good = false; break; }
             __builtin_amdgcn_s_sleep(kSpinSleep);
             magic = xwg_load64(&ctrl->magic);
         }
@@ -548,7 +549,7 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
             __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             for (uint32_t spin = 0;; ++spin) {
                 if (__hip_atomic_load(&ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
-                if (spin >= kSpinLimit) { good = false; break; }
+                if (spin >= spin_limit) { good = false; break; }
                 __builtin_amdgcn_s_sleep(kSpinSleep);
             }
         }
@@ -586,7 +587,7 @@ __device__ __forceinline__ void publish_word(WordRecord *r, uint64_t nonce, uint
     xwg_store64(&r->check, word_check(value, nonce, rec));
 }
 // polled by the calling lane until it passes (bounded); false when the wait ran out
-__device__ __forceinline__ bool acquire_word(WordRecord *r, uint64_t nonce, uint64_t rec, uint64_t &value) {
+__device__ __forceinline__ bool acquire_word(WordRecord *r, uint64_t nonce, uint64_t rec, uint64_t &value, uint32_t spin_limit) {
     for (uint32_t spin = 0;; ++spin) {
         value = xwg_load64(&r->value);
         const uint64_t ck = xwg_load64(&r->check);
@@ -594,7 +595,7 @@ __device__ __forceinline__ bool acquire_word(WordRecord *r, uint64_t nonce, uint
             xwg_store64(&r->check, 0ull);
             return true;
         }
-        if (spin >= kSpinLimit) return false;
+        if (spin >= spin_limit) return false;
         __builtin_amdgcn_s_sleep(kSpinSleep);
     }
 }

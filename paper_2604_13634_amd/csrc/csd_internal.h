@@ -102,7 +102,9 @@ struct EpilogueArgs {
     // single-launch step only
     StepRecord *records;     // [rows][nsplit]: one per streaming workgroup
     StepControl *ctrl;
-    uint64_t nonce;          // per-call number behind the records' tags
+    uint64_t nonce;          // per-call number behind the records' check words
+    uint64_t reader_nonce;   // the same number as the readers use it (a test hook can make them differ: nothing then passes)
+    uint32_t spin_limit;     // polls after which a wait inside the launch gives up
     int n_stream_wgs;        // workgroups [0, n_stream_wgs) stream rows, the rest take sequences
     int update_here;         // 1: the sequence waves apply their own increments after a barrier among their workgroups
 };
@@ -168,6 +170,8 @@ struct SampledArgs {
     WordRecord *draws;         // [B][k+1] the draws, published inside the last launch
     StepControl *ctrl;         // barrier state of the last launch's sequence workgroups
     uint64_t nonce;            // per-call number behind the draws' check words
+    uint64_t reader_nonce;     // the same number as the readers use it (a test hook can make them differ)
+    uint32_t spin_limit;       // polls after which a wait inside the launch gives up
     int n_loc_wgs;             // workgroups of the last launch that invert running sums; the sequence workgroups follow
     int update_here;           // 1: the sequence waves apply their own increments after a barrier among their workgroups
 };

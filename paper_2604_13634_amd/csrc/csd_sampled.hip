@@ -376,7 +376,7 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
     if (lane < K1) {
         uint64_t v = 0;
         const uint64_t rec = (uint64_t)b * K1 + lane;
-        got = acquire_word(a.draws + rec, a.nonce, rec, v);
+        got = acquire_word(a.draws + rec, a.reader_nonce, rec, v, a.spin_limit);
         t = (int)(uint32_t)v;
     }
     stalled = __builtin_amdgcn_ballot_w64(!got) != 0ull;
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
         }
     }
     sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
-                                  dv, &verdict);
+                                  dv, &verdict, a.spin_limit);
 }
 
 }  // namespace

@@ -418,7 +418,7 @@ __device__ __forceinline__ void publish_record(StepRecord *r, uint64_t nonce, ui
 // of the wave together.
 template <int N>
 __device__ __forceinline__ bool acquire_records(StepRecord *row_rec, uint64_t rec0, int G, int gs, int u0, uint32_t want,
-                                                uint64_t nonce, RowPartial (&q)[N]) {
+                                                uint64_t nonce, uint32_t spin_limit, RowPartial (&q)[N]) {
     uint32_t pend = want;
     for (uint32_t spin = 0;; ++spin) {
         uint64_t w0[N], w1[N], ck[N];
@@ -446,7 +446,7 @@ __device__ __forceinline__ bool acquire_records(StepRecord *row_rec, uint64_t re
             }
         }
         if (__builtin_amdgcn_ballot_w64(pend != 0u) == 0ull) return true;
-        if (spin >= kSpinLimit) return false;
+        if (spin >= spin_limit) return false;
         __builtin_amdgcn_s_sleep(kSpinSleep);
     }
 }
@@ -455,7 +455,7 @@ __device__ __forceinline__ bool acquire_records(StepRecord *row_rec, uint64_t re
 // arithmetic of the two-launch combine, in its order.
 template <int NB>
 __device__ __forceinline__ bool acquire_row_stats(StepRecord *row_rec, uint64_t rec0, int P, int G, int gs, bool active,
-                                                  uint64_t nonce, float &gm, int &t, double &S) {
+                                                  uint64_t nonce, uint32_t spin_limit, float &gm, int &t, double &S) {
     RowPartial q[NB];
     uint32_t want = 0;
 #pragma unroll
@@ -463,7 +463,7 @@ __device__ __forceinline__ bool acquire_row_stats(StepRecord *row_rec, uint64_t 
         q[u] = empty_partial();
         if (active && gs + u * G < P) want |= 1u << u;
     }
-    const bool ok = acquire_records<NB>(row_rec, rec0, G, gs, 0, want, nonce, q);
+    const bool ok = acquire_records<NB>(row_rec, rec0, G, gs, 0, want, nonce, spin_limit, q);
     gm = -INFINITY;
     t = 0x7fffffff;
     S = 0.0;
@@ -502,7 +502,7 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
         double S;
         bool ok;
         if (per_lane <= 4) {                         // every benchmark shape: one round trip for the whole sequence
-            ok = acquire_row_stats<4>(row_rec, rec0, P, G, gs, active, a.nonce, gm, t, S);
+            ok = acquire_row_stats<4>(row_rec, rec0, P, G, gs, active, a.reader_nonce, a.spin_limit, gm, t, S);
         } else {
             // many partials per lane (a huge vocabulary under a small batch): wait for them four at a time, keeping
             // the running maximum only, then take the sums in a second pass over the (now plainly readable) words
@@ -519,7 +519,7 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
                     if (active && gs + (u0 + u) * G < P) want |= 1u << u;
                 }
                 if (__builtin_amdgcn_ballot_w64(want != 0u) != 0ull)
-                    ok = acquire_records<4>(row_rec, rec0, G, gs, u0, want, a.nonce, q4) && ok;
+                    ok = acquire_records<4>(row_rec, rec0, G, gs, u0, want, a.reader_nonce, a.spin_limit, q4) && ok;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (q4[u].m > gm || (q4[u].m == gm && q4[u].idx < t)) t = q4[u].idx;
@@ -553,7 +553,7 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
     }
 
     sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
-                                  dv, verdict);
+                                  dv, verdict, a.spin_limit);
 }
 
 template <int DT>

@@ -179,6 +179,90 @@ def test_masked_vocab_and_extreme_ranges(dtype):
     _check_against_oracle(z, draft)
 
 
+@pytest.mark.parametrize("dtype,B,k,V", [("f32", 1, 4, 1 << 20), ("bf16", 1, 6, 1000003), ("f32", 2, 7, 600011),
+                                         ("bf16", 257, 3, 4100), ("f32", 1030, 2, 2500)])
+def test_few_sequences_over_huge_vocabularies_and_batches_past_the_barrier(dtype, B, k, V):
+    """Shapes off the benchmark's beaten path of the single-launch step: one or two sequences over a vocabulary so
+    large that a row is cut into more than a hundred workgroups (a sequence wave then takes its rows' records in
+    several rounds and re-reads them for the sums), and batches of more than 256 sequences (more sequence
+    workgroups than may wait for each other: the updates go through the log and a second launch).  Three steps
+    each, memory evolving, everything compared with the oracle."""
+    rng = np.random.default_rng(B * 1000 + k)
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    bf = None
+    pool = rng.integers(0, V, 24)                                   # few tokens, so that pairs recur and get rescued
+    for step in range(3):
+        z = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+        top = pool[rng.integers(0, 24, (B, k + 1))]
+        np.put_along_axis(z, top[..., None], z.max(-1, keepdims=True) + 4.0, axis=-1)
+        draft = np.where(rng.random((B, k)) < 0.5, top[:, :k], pool[rng.integers(0, 24, (B, k))]).astype(np.int32)
+        zd = z[:, :k]                                               # a view: a divergent draft token sits 0.5 below the top
+        off = np.where(draft == top[:, :k], 0.0, 0.5).astype(np.float32)
+        np.put_along_axis(zd, draft[..., None].astype(np.int64), (zd.max(-1) - off)[..., None], axis=-1)
+        if dtype == "bf16":
+            z = f32_to_bf16_bits(z).reshape(z.shape)
+        bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), 0.3, 1, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = orc.verify_step(np.ascontiguousarray(z), draft, tau=np.float32(0.3), lam=1)
+        compare_step(res, bf, "%s B=%d k=%d V=%d step %d" % (dtype, B, k, V, step))
+        compare_table(ocm, orc, "B=%d V=%d step %d" % (B, V, step))
+    assert int(bf.status[csd.CSD_STATUS_STALLED]) == 0 and len(orc.T) > 0
+
+
+def test_waits_that_run_out_are_reported_and_leave_everything_usable():
+    """The waits inside the single-launch step are bounded.  A test hook of the library (not part of csd.h) makes
+    the sequence waves look for records under another per-call number than the streaming workgroups publish them
+    under, and cuts the bound to 64 polls: every wait runs out.  The kernels end normally, every sequence is counted
+    in status[CSD_STATUS_STALLED] and reports accept_len 0 / next_token -1, the memory is untouched - and the next
+    ordinary call on the same buffers and workspace agrees with the oracle again.  Same for the sampled step."""
+    import ctypes
+    from gen.workload import SampledWorkload
+    from parity_util import check_sampled_step, settle_uniforms
+    lib = csd.load_library()
+    lib.csd_test_set_wait_rules.restype = None
+    lib.csd_test_set_wait_rules.argtypes = [ctypes.c_uint32, ctypes.c_uint64]
+    w = Workload(CONFIGS[1], V=9001, B=10, n_pairs=16)
+    ws = SampledWorkload(CONFIGS[1], V=9001, B=10, n_pairs=16)
+    cfg = w.cfg
+    ocm, ocm_s = csd.new_ocm(1 << 10), csd.new_ocm(1 << 10)
+    orc, orc_s = O.CSDOracle(), O.CSDOracle()
+    bf = sb = None
+    for step in range(4):
+        z, draft = w.step(step)
+        zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+        zp, zq, sdraft, ua, ud = ws.sampled_step(step)
+        ua, ud = settle_uniforms(zp, zq, sdraft, 0.9, ua, ud, seed=step)
+        sargs = (to_device_logits(zp), to_device_logits(zq), torch.from_numpy(sdraft).cuda(), 0.9, torch.from_numpy(ua).cuda(),
+                 torch.from_numpy(ud).cuda(), cfg.tau, 1, ocm_s)
+        if step == 2:                                   # in the middle of the stream: both paths stall once
+            before, before_s = decode_ocm(ocm), decode_ocm(ocm_s)
+            lib.csd_test_set_wait_rules(64, 0x5EEDF00D)
+            try:
+                bf.status.zero_()
+                sb.status.zero_()
+                csd.csd_verify(zt, dt, cfg.tau, 1, ocm, buffers=bf)
+                csd.csd_verify_sampled(*sargs, buffers=sb)
+                torch.cuda.synchronize()
+            finally:
+                lib.csd_test_set_wait_rules(0, 0)
+            for b_, name in ((bf, "greedy"), (sb, "sampled")):
+                st = b_.status.cpu().numpy().view(np.uint32)
+                assert st[csd.CSD_STATUS_STALLED] == cfg.B and st[csd.CSD_STATUS_COUNTED] == 0, (name, st)
+                assert b_.accept_len.cpu().tolist() == [0] * cfg.B and b_.next_token.cpu().tolist() == [-1] * cfg.B, name
+            assert decode_ocm(ocm) == before and decode_ocm(ocm_s) == before_s
+            bf.status.zero_()
+            sb.status.zero_()
+        bf = csd.csd_verify(zt, dt, cfg.tau, 1, ocm, buffers=bf)
+        sb = csd.csd_verify_sampled(*sargs, buffers=sb)
+        torch.cuda.synchronize()
+        compare_step(orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=1), bf, "greedy step %d" % step)
+        check_sampled_step(orc_s, zp, zq, sdraft, 0.9, ua, ud, np.float32(cfg.tau), 1, sb, "sampled step %d" % step)
+        compare_table(ocm, orc, "greedy step %d" % step)
+        compare_table(ocm_s, orc_s, "sampled step %d" % step)
+    assert int(bf.status[csd.CSD_STATUS_STALLED]) == 0 and int(sb.status[csd.CSD_STATUS_STALLED]) == 0
+
+
 def test_many_rows_and_k_limits():
     rng = np.random.default_rng(21)
     for B, k, V in [(1, 0, 5000), (3, 63, 700), (700, 1, 300), (33, 15, 2500)]:
