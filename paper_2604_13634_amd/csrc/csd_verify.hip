@@ -400,6 +400,7 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 // resident early take places from the streaming workgroups: 1-5 us slower on four of the five shapes); waiting
 // on one record per sequence before polling all (no gain once records are one per workgroup); per-wave records
 // (three rounds of loads at k = 8).
+
 // the check word of a record: a hash of its two data words, of the call's number and of the record's index
 __device__ __forceinline__ uint64_t record_check(uint64_t w0, uint64_t w1, uint64_t nonce, uint64_t rec) {
     return mix64(w0 + mix64(w1 ^ (nonce + rec * 0x9E3779B97F4A7C15ull))) | 1ull;   // never zero: a zeroed record does not pass
