@@ -45,6 +45,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak, GB/s
 STEP_KERNEL = "verify_step_kernel"
 STREAM_KERNEL = "row_partials_kernel"
+PROBE_TILE_BYTES = 32768       # the streaming pass (and the probe) move whole 32 KiB tiles
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_verify_step.json")
 COPY_BYTES = 1 << 30           # the calibration copy moves 1 GiB in and 1 GiB out
 RAMP_S = 0.05                  # untimed load before every timed loop
@@ -231,23 +232,32 @@ def measure_greedy(cfg, steps, warmup, ring_bytes, gen_threads, full=False, keep
         res["streaming_pass_alone"] = {"kernel": "%s<%s>" % (STREAM_KERNEL, cfg.dtype), "kernel_ms": k_ms,
                                        "GBps": alg_bytes / (k_ms * 1e-3) / 1e9,
                                        "frac": alg_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        # read-only probe with the same load shape: what this access pattern can reach on this machine
+        # read-only probe: the streaming pass's loads and nothing else, dealt to the product's number of workgroups
+        # per row and to two other deals (one tile per workgroup, four tiles); the fastest is the ceiling
         probe = ctypes.CDLL(os.path.join(ROOT, "paper_2604_13634_amd", "libcsd_probe.so"))
         probe.csd_probe_read.restype = ctypes.c_int64
         probe.csd_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p]
         sink = torch.zeros(4, dtype=torch.int32, device="cuda")
         nsplit = csd.csd_row_partials_per_row(rows, cfg.V, dt) // 4
-        read = [0]
+        ntiles = max(1, (cfg.V * cfg.itemsize) // PROBE_TILE_BYTES)
+        shapes = {}
+        for ns in sorted({nsplit, ntiles, (ntiles + 3) // 4}):
+            read = [0]
 
-        def pr(i):
-            z = ring[i % n_ring][0]
-            read[0] = probe.csd_probe_read(z.data_ptr(), z.stride(1) * cfg.itemsize, rows, cfg.V * cfg.itemsize, nsplit,
-                                           sink.data_ptr(), torch.cuda.current_stream().cuda_stream or None)
-        pr(0)
-        if read[0] > 0:
-            _, p_ms = timed(pr, steps, warmup)
-            res["read_probe"] = {"bytes_per_launch": read[0], "kernel_ms": p_ms, "GBps": read[0] / (p_ms * 1e-3) / 1e9}
+            def pr(i, ns=ns):
+                z = ring[i % n_ring][0]
+                read[0] = probe.csd_probe_read(z.data_ptr(), z.stride(1) * cfg.itemsize, rows, cfg.V * cfg.itemsize, ns,
+                                               sink.data_ptr(), torch.cuda.current_stream().cuda_stream or None)
+            pr(0)
+            if read[0] > 0:
+                _, p_ms = timed(pr, steps, warmup)
+                shapes[ns] = {"workgroups_per_row": ns, "bytes_per_launch": read[0], "kernel_ms": p_ms,
+                              "GBps": read[0] / (p_ms * 1e-3) / 1e9}
+        if shapes:
+            best = max(shapes.values(), key=lambda e: e["GBps"])
+            res["read_probe"] = dict(best, product_workgroups_per_row=nsplit,
+                                     all_deals={str(ns): round(e["GBps"], 1) for ns, e in shapes.items()})
     del ring
     torch.cuda.empty_cache()
     return res, host, w

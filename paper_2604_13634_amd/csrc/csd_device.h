@@ -521,14 +521,20 @@ struct Divergence {
 // (all but the rare lost insert are known; their atomics need no answer and travel while the workgroup waits),
 // and - update_here - the step's increments are applied after a barrier of the launch's `total` sequence
 // workgroups: every lookup of the step before any update of the step.
-//   An absent pair's slot is claimed at once (count zero: no lookup of the step reads it differently); the
-//   compare-and-swap is in flight during the barrier.  This workgroup's lookups have returned when it counts itself
-//   in (their values were used by the caller); its stores may still be on their way, nobody waits for them.
-//   The counter in the control head must be zero when a launch begins; `magic` (read early by thread 0) says that
-//   it has been set up, by the first workgroup of this launch at the latest.  Each workgroup also counts itself
-//   out, off the updates' path: the one that brings the counter to 2 * total is the last to have read it, and
-//   leaves it at zero for the next call.
-__device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t magic, uint32_t total, bool update_here,
+//   This workgroup's lookups have returned when it counts itself in (their values were used by the caller); its
+//   stores may still be on their way, nobody waits for them.  An absent pair's slot is claimed while the barrier
+//   is pending (count zero: no lookup of the step reads it differently), so the compare-and-swap and the barrier
+//   share their wait.
+//   The counter behind the barrier is zeroed by the first workgroup of the same launch, which then writes
+//   `ready_value` (derived from the call's number) into the control head; thread 0 here asked for that word early
+//   (`ready_seen`) and counts itself in only once it holds.  After the barrier every workgroup has seen it, and the
+//   first sequence workgroup clears it, so that a replay of the same launch (same number) waits for its own
+//   set-up; a workgroup whose wait ran out clears it as well.  Nothing here needs an answer after the barrier:
+//   the increments and the clearing store travel while the kernel ends.
+__device__ __forceinline__ uint64_t step_ready_value(uint64_t nonce) { return mix64(nonce ^ 0x5244595f43534431ull) | 1ull; }
+
+__device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t ready_seen, uint64_t ready_value,
+                                                              bool first_sequence_workgroup, uint32_t total, bool update_here,
                                                               uint64_t *ocm, uint64_t capacity, uint32_t *status,
                                                               BlockCounters &counters, const Divergence &dv, int *verdict,
                                                               uint32_t spin_limit) {
@@ -536,45 +542,47 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
     if (status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
         atomicAdd(&status[threadIdx.x], counters.v[threadIdx.x]);
     if (!update_here) return;
+    bool good = true;
+    if (threadIdx.x == 0) {
+        for (uint32_t spin = 0; ready_seen != ready_value; ++spin) {
+            if (spin >= spin_limit) { good = false; break; }
+            __builtin_amdgcn_s_sleep(kSpinSleep);
+            ready_seen = xwg_load64(&ctrl->ready);
+        }
+        if (good) __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     OcmClaim claim = {CSD_OCM_EMPTY, false, false};
     if (dv.counted) claim = ocm_claim_after_probe(ocm, dv.key, dv.probe);
     if (threadIdx.x == 0) {
-        bool good = true;
-        for (uint32_t spin = 0; magic != kStepMagic; ++spin) {
-            if (spin >= spin_limit) { good = false; break; }
-            __builtin_amdgcn_s_sleep(kSpinSleep);
-            magic = xwg_load64(&ctrl->magic);
-        }
         if (good) {
-            __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             for (uint32_t spin = 0;; ++spin) {
                 if (__hip_atomic_load(&ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
                 if (spin >= spin_limit) { good = false; break; }
                 __builtin_amdgcn_s_sleep(kSpinSleep);
             }
         }
-        if (!good && status != nullptr) atomicAdd(&status[CSD_STATUS_STALLED], 1u);
+        if (!good) {
+            xwg_store64(&ctrl->ready, 0ull);
+            if (status != nullptr) atomicAdd(&status[CSD_STATUS_STALLED], 1u);
+        } else if (first_sequence_workgroup) {
+            xwg_store64(&ctrl->ready, 0ull);
+        }
         *verdict = good ? 1 : 0;
     }
     barrier_lds_only();
-    const bool passed = *verdict != 0;
-    if (passed && dv.counted) {
+    if (*verdict != 0 && dv.counted) {
         if (!ocm_add_one_after_claim(ocm, capacity, dv.key, dv.probe, claim) && status != nullptr)
             atomicAdd(&status[CSD_STATUS_DROPPED], 1u);
     }
-    if (threadIdx.x == 0 && passed) {
-        const uint32_t old = __hip_atomic_fetch_add(&ctrl->arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old == 2u * total - 1u) __hip_atomic_store(&ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
 }
 
-// The first workgroup of a launch whose sequence workgroups will use the barrier: the counter starts at zero,
-// and only then does the magic say so (called by one thread).
-__device__ __forceinline__ void step_control_setup(StepControl *ctrl) {
-    if (xwg_load64(&ctrl->magic) == kStepMagic) return;
+// The first workgroup of a launch whose sequence workgroups will use the barrier (called by one thread): the
+// counter is zero, and only then does the control head say so.  The launch before has ended, nothing else
+// touches the head.
+__device__ __forceinline__ void step_control_setup(StepControl *ctrl, uint64_t ready_value) {
     __hip_atomic_store(&ctrl->arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the zero is acknowledged before the magic leaves
-    xwg_store64(&ctrl->magic, kStepMagic);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the zero is acknowledged before the word leaves
+    xwg_store64(&ctrl->ready, ready_value);
 }
 
 // Published words (WordRecord): same rules as StepRecord - a reader takes one once the check holds and zeroes the

@@ -50,14 +50,14 @@ struct WordRecord {
 };
 
 // Head of the csd_verify workspace.  `arrivals` is the counter behind the barrier of the sequence workgroups;
-// it is zero between calls (the last workgroup through resets it).  `magic` says that this has been set up:
-// the first workgroup of a launch that finds another value there zeroes the counter and writes the magic.
+// the first workgroup of every launch that uses the barrier zeroes it and then writes a word derived from the
+// call's number into `ready`; the sequence workgroups count themselves in once they see that word, and clear
+// it after the barrier.  The head may hold anything before a call.
 struct StepControl {
-    uint64_t magic;
+    uint64_t ready;
     uint32_t arrivals;
     uint32_t pad;
 };
-constexpr uint64_t kStepMagic = 0x3153444e56445343ull;
 
 // csd_verify workspace: [control | records | rejection log].  Nothing but the control head outlives a call.
 struct WorkspaceLayout {

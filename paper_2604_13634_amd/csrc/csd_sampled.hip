@@ -455,7 +455,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
     const int wave = threadIdx.x >> 6;
     const int K1 = a.k + 1;
     if ((int)blockIdx.x < a.n_loc_wgs) {
-        if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl);
+        if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl, step_ready_value(a.nonce));
         const int64_t j = (int64_t)blockIdx.x * kSegBlockWaves + wave;
         if (j >= (int64_t)a.B * K1) return;
         const int result = locate_draw<DT>(a, j, lane);
@@ -465,8 +465,8 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
     const int wg = (int)blockIdx.x - a.n_loc_wgs;
     const int n_seq_wgs = (int)gridDim.x - a.n_loc_wgs;
     const int b = wg * kSegBlockWaves + wave;
-    uint64_t magic = 0;
-    if (a.update_here && threadIdx.x == 0) magic = xwg_load64(&a.ctrl->magic);
+    uint64_t ready_seen = 0;
+    if (a.update_here && threadIdx.x == 0) ready_seen = xwg_load64(&a.ctrl->ready);
     block_counters_clear(counters);
     Divergence dv;
     dv.counted = false;
@@ -481,8 +481,8 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
             atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
         }
     }
-    sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
-                                  dv, &verdict, a.spin_limit);
+    sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)n_seq_wgs,
+                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, dv, &verdict, a.spin_limit);
 }
 
 }  // namespace

@@ -388,8 +388,9 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 // wait for each other) each workgroup counts itself in on the control head once its lookups are done, waits
 // until all have, and then every lane adds its own pair straight to the table at the slot its lookup ended at
 // (the slot of an absent pair is claimed with count zero while the workgroup waits): all lookups of the step
-// precede all its updates, and no log is re-read.  Each workgroup counts itself out as well; the last one out
-// resets the counter for the next call.
+// precede all its updates, and no log is re-read.  The first workgroup of the launch zeroes that counter and
+// then says so in the control head; the sequence workgroups count themselves in only after seeing that, and
+// clear the word after the barrier (so nothing in the workspace has to survive from one call to the next).
 //
 // Measured against the two-launch form (streaming kernel, then a kernel of sequence waves) on the five
 // benchmark shapes: 15.0 -> 10.3, 17.8 -> 13.2, 29.3 -> 23.8, 68.2 -> 59.8 and 106.7 -> 104.5 microseconds per
@@ -479,8 +480,8 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
     const int b = wg * kStepSeqWaves + (threadIdx.x >> 6);
     const int k = a.k, K1 = a.k + 1;
     // thread 0 will need the control head set up: ask early, look at the answer late
-    uint64_t magic = 0;
-    if (a.update_here && threadIdx.x == 0) magic = xwg_load64(&a.ctrl->magic);
+    uint64_t ready_seen = 0;
+    if (a.update_here && threadIdx.x == 0) ready_seen = xwg_load64(&a.ctrl->ready);
     block_counters_clear(counters);
 
     Divergence dv;
@@ -553,8 +554,8 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
         }
     }
 
-    sequence_counters_and_updates(a.ctrl, magic, (uint32_t)n_seq_wgs, a.update_here != 0, a.ocm, a.capacity, a.status, counters,
-                                  dv, verdict, a.spin_limit);
+    sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)n_seq_wgs,
+                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, dv, verdict, a.spin_limit);
 }
 
 template <int DT>
@@ -571,7 +572,7 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void verify_step_kernel
     const int split = blockIdx.x - row * nsplit;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl);
+    if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl, step_ready_value(a.nonce));
     const char *rowp = src.base0 + (int64_t)row * src.pitch0;
     const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
     // The four waves of the workgroup (they sweep the same tiles and end together) leave ONE record: fewer records
@@ -611,10 +612,18 @@ StreamPlan make_stream_plan(int rows, int V, int dtype) {
     p.elems_per_chunk = (dtype == CSD_DTYPE_F32) ? 4 : 8;
     p.nchunks = (V + p.elems_per_chunk - 1) / p.elems_per_chunk;
     p.ntiles_row = (V / p.elems_per_chunk) / kTileChunks;
-    // Workgroups per row: one tile each while the launch is small (latency matters, fill the chip),
-    // about four tiles each once there are thousands of tiles (fewer partials and tickets per byte).
-    const int64_t tiles_total = (int64_t)rows * (p.ntiles_row > 0 ? p.ntiles_row : 1);
-    const int tiles_per_group = tiles_total >= 16384 ? 4 : (tiles_total >= 4096 ? 2 : 1);
+    // Workgroups per row.  Two tiles per workgroup measured best from the smallest benchmark shape to the largest
+    // (one tile: a third more records to publish and to wait for, and 4 - 6 % slower at every size; four: 0.5 - 2 %
+    // slower on the two big shapes).  The exception is a launch that two tiles leave just too large to be resident
+    // at once (four workgroups per compute unit): three or four tiles then bring it under that line, and no
+    // second round of workgroups has to be dealt out (256 rows of 9 tiles: 22.4 -> 21.9 microseconds per step).
+    const int ntr = p.ntiles_row > 0 ? p.ntiles_row : 1;
+    const int64_t resident = 4 * 256;
+    int tiles_per_group = 2;
+    if ((int64_t)rows * ((ntr + 1) / 2) > resident) {
+        for (int t = 3; t <= 4; ++t)
+            if ((int64_t)rows * ((ntr + t - 1) / t) <= resident) { tiles_per_group = t; break; }
+    }
     int nsplit = (p.ntiles_row + tiles_per_group - 1) / tiles_per_group;
     if (nsplit < 1) nsplit = 1;
     p.nsplit = nsplit;

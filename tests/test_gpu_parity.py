@@ -213,8 +213,9 @@ def test_few_sequences_over_huge_vocabularies_and_batches_past_the_barrier(dtype
 def test_waits_that_run_out_are_reported_and_leave_everything_usable():
     """The waits inside the single-launch step are bounded.  A test hook of the library (not part of csd.h) makes
     the sequence waves look for records under another per-call number than the streaming workgroups publish them
-    under, and cuts the bound to 64 polls: every wait runs out.  The kernels end normally, every sequence is counted
-    in status[CSD_STATUS_STALLED] and reports accept_len 0 / next_token -1, the memory is untouched - and the next
+    under, and cuts the bound to 64 polls: every wait runs out.  The kernels end normally, status[CSD_STATUS_STALLED]
+    counts one wait per sequence (its rows' records) and one per sequence workgroup of four (the barrier before the
+    updates), every sequence reports accept_len 0 / next_token -1, the memory is untouched - and the next
     ordinary call on the same buffers and workspace agrees with the oracle again.  Same for the sampled step."""
     import ctypes
     from gen.workload import SampledWorkload
@@ -248,7 +249,7 @@ def test_waits_that_run_out_are_reported_and_leave_everything_usable():
                 lib.csd_test_set_wait_rules(0, 0)
             for b_, name in ((bf, "greedy"), (sb, "sampled")):
                 st = b_.status.cpu().numpy().view(np.uint32)
-                assert st[csd.CSD_STATUS_STALLED] == cfg.B and st[csd.CSD_STATUS_COUNTED] == 0, (name, st)
+                assert st[csd.CSD_STATUS_STALLED] == cfg.B + (cfg.B + 3) // 4 and st[csd.CSD_STATUS_COUNTED] == 0, (name, st)
                 assert b_.accept_len.cpu().tolist() == [0] * cfg.B and b_.next_token.cpu().tolist() == [-1] * cfg.B, name
             assert decode_ocm(ocm) == before and decode_ocm(ocm_s) == before_s
             bf.status.zero_()
