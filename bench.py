@@ -56,7 +56,8 @@ def kernel_fingerprint() -> str:
     """Hash of everything that shapes the kernels and their launch plan: stored counter readings apply to one version only."""
     h = hashlib.sha256()
     for rel in ("paper_2604_13634_amd/csrc/csd_verify.hip", "paper_2604_13634_amd/csrc/csd_sampled.hip",
-                "paper_2604_13634_amd/csrc/csd_device.h", "paper_2604_13634_amd/csrc/csd_internal.h",
+                "paper_2604_13634_amd/csrc/csd_stream.h", "paper_2604_13634_amd/csrc/csd_device.h",
+                "paper_2604_13634_amd/csrc/csd_internal.h",
                 "paper_2604_13634_amd/csrc/csd_api.hip", "include/csd.h", "paper_2604_13634_amd/build.py"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())

@@ -135,9 +135,8 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  * bounded: see CSD_STATUS_STALLED.
  * Scratch
  *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; needs no
- *                         initialisation (any content will do the first time; the library keeps a few words of
- *                         state in it between calls, so do not write to it in between).  Two calls in flight
- *                         must not share a workspace.
+ *                         initialisation and carries nothing from one call to the next (any content will do).
+ *                         Two calls in flight must not share a workspace.
  * B == 0 is a valid no-op.  k == 0 verifies nothing and returns the argmax of the single row.
  */
 int csd_verify(const void *logits, int dtype, int64_t row_stride, const int32_t *draft, int B, int k, int V, float tau,

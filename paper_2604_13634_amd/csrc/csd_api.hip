@@ -272,7 +272,7 @@ static SampledWorkspace sampled_layout(const StreamPlan &plan, int B, int k, int
     const size_t K1 = (size_t)k + 1;
     w.ticket_off = 0;
     w.partials_off = 256;
-    w.rows_off = up(w.partials_off + (size_t)plan.rows * plan.partials_per_row * sizeof(RowPartial));
+    w.rows_off = up(w.partials_off + (size_t)plan.rows * plan.nsplit * sizeof(StepRecord));   // one record per streaming workgroup
     w.work_off = up(w.rows_off + (size_t)B * K1 * sizeof(DrawRow));
     w.segsum_off = up(w.work_off + (size_t)B * K1 * sizeof(int32_t));
     w.zpd_off = up(w.segsum_off + (size_t)B * K1 * (size_t)nseg * sizeof(float));
@@ -343,11 +343,12 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.lambda = lambda;
     a.ocm = ocm;
     a.capacity = capacity;
-    a.partials = (const RowPartial *)(wsp + ws.partials_off);
-    a.partials_per_row = plan.partials_per_row;
+    a.records = (StepRecord *)(wsp + ws.partials_off);
+    a.nsplit = plan.nsplit;
+    a.n_stream_wgs = plan.rows * plan.nsplit;
     a.nseg = nseg;
     a.rows = (DrawRow *)(wsp + ws.rows_off);
-    a.work_count = (uint32_t *)(wsp + ws.ticket_off) + 1;
+    a.list_ctrl = (StepControl *)(wsp + ws.ticket_off);
     a.work_rows = (int32_t *)(wsp + ws.work_off);
     a.segsum = (float *)(wsp + ws.segsum_off);
     a.pos_zpd = (float *)(wsp + ws.zpd_off);
@@ -363,9 +364,8 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.pos_flags = pos_flags;
     a.rej_log = rej_log ? rej_log : (apply ? (uint64_t *)(wsp + ws.log_off) : nullptr);
     a.status = status;
-    a.batch_ticket = (uint32_t *)(wsp + ws.ticket_off);
     a.draws = (WordRecord *)(wsp + ws.draws_off);
-    a.ctrl = (StepControl *)(wsp + ws.ticket_off + 16);   // behind the two words the first launch zeroes
+    a.ctrl = (StepControl *)(wsp + ws.ticket_off + sizeof(StepControl));   // behind the list's control head
     a.nonce = next_call_number();
     a.reader_nonce = a.nonce ^ g_reader_nonce_xor.load(std::memory_order_relaxed);
     a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
@@ -378,9 +378,7 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
 
     const StreamSource src = {(const char *)target_logits, target_row_stride * (int64_t)esz, rows_p,
                               (const char *)draft_logits, draft_row_stride * (int64_t)esz, scale};
-    if (launch_row_partials(src, dtype, V, plan, (RowPartial *)(wsp + ws.partials_off), a.batch_ticket, st) != hipSuccess)
-        return CSD_EHIP;
-    if (launch_sampled_tail(a, st) != hipSuccess) return CSD_EHIP;
+    if (launch_sampled_step(src, a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_in_finish) {
         if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, nullptr, status, st) != hipSuccess)
             return CSD_EHIP;

@@ -517,6 +517,22 @@ struct Divergence {
 };
 
 
+// A sequence whose wait inside the launch ran out: nothing accepted, no emitted token, no position flagged, and
+// no divergence in the log (a later bulk update must not apply what an earlier step left there).  Called by
+// the sequence's wave; the caller counts it in CSD_STATUS_STALLED.
+__device__ __forceinline__ void report_stalled_sequence(int32_t *accept_len, int32_t *next_token, uint8_t *pos_flags,
+                                                        uint64_t *rej_log, int b, int k, int lane) {
+    if (lane == 0) {
+        accept_len[b] = 0;
+        next_token[b] = -1;
+    }
+    if (lane < k) {
+        const int64_t o = (int64_t)b * k + lane;
+        if (pos_flags) pos_flags[o] = 0;
+        if (rej_log) xwg_store64(&rej_log[o], CSD_OCM_EMPTY);
+    }
+}
+
 // The end of a sequence workgroup's step, called by all its threads: the per-workgroup status counters leave
 // (all but the rare lost insert are known; their atomics need no answer and travel while the workgroup waits),
 // and - update_here - the step's increments are applied after a barrier of the launch's `total` sequence

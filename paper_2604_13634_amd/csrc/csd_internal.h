@@ -123,7 +123,8 @@ struct StreamSource {
 // ---- verification at a sampling temperature (csd_sampled.hip)
 // What the residual kernels need for one draw row (a rejected draft position, or the bonus row).
 struct DrawRow {
-    int32_t need;      // 0: nothing is drawn for this row
+    int32_t need;      // 0: nothing is drawn for this row; 1: a draw; 2 (on a sequence's bonus row only): the
+                       // sequence's first-launch wait ran out, nothing of it is drawn and its loop is not run
     int32_t fallback;  // the target row's argmax: reported when the residual has no mass, or the draft id was invalid
     float cp, fp;      // p_v = 2^(z_v * scale - cp) * fp
     float cq, fq;      // q_v likewise; unused for the bonus row, which draws from p itself
@@ -146,11 +147,13 @@ struct SampledArgs {
     uint32_t lambda;
     uint64_t *ocm;
     uint64_t capacity;
-    const RowPartial *partials;   // target rows first, then draft rows
-    int partials_per_row;
+    StepRecord *records;       // one per streaming workgroup of the first launch: target rows first, then draft rows
+    int nsplit;                // streaming workgroups (records) per row
+    int n_stream_wgs;          // streaming workgroups of the first launch; its acceptance-test workgroups follow
     int nseg;                  // segments per row
     DrawRow *rows;             // [B][k+1]
-    uint32_t *work_count;      // [1] number of rows that need a draw (the word after the batch ticket)
+    StepControl *list_ctrl;    // `arrivals` is the number of rows that need a draw; zeroed and announced by the
+                               // first launch's first workgroup, the announcement cleared by the second launch
     int32_t *work_rows;        // [B][k+1] their indices, in no particular order
     float *segsum;             // [B][k+1][nseg]
     float *pos_zpd;            // [B][k] target logit of the draft token
@@ -166,7 +169,6 @@ struct SampledArgs {
     uint8_t *pos_flags;
     uint64_t *rej_log;
     uint32_t *status;
-    uint32_t *batch_ticket;    // [2]: unused word, and the length of the list of rows to draw; zeroed by the first launch
     WordRecord *draws;         // [B][k+1] the draws, published inside the last launch
     StepControl *ctrl;         // barrier state of the last launch's sequence workgroups
     uint64_t nonce;            // per-call number behind the draws' check words
@@ -183,7 +185,7 @@ struct SampledWorkspace {
 int sampled_locate_workgroups(int B, int k);
 int sampled_sequence_workgroups(int B);
 int sampled_segments(int V, int dtype);
-hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream);
+hipError_t launch_sampled_step(const StreamSource &src, const SampledArgs &a, hipStream_t stream);
 
 // kernel launchers (enqueue only; return hipGetLastError())
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,

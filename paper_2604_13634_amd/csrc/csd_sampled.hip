@@ -23,7 +23,7 @@
 //      sequence workgroups (the same tail as the greedy step's single launch).
 // Positions whose acceptance test fails are all drawn (the draws do not depend on each other), although
 // the loop may stop before it reaches some of them; so is the bonus token of every sequence.
-#include "csd_device.h"
+#include "csd_stream.h"
 
 namespace csd {
 namespace {
@@ -89,10 +89,11 @@ __device__ __forceinline__ double wave_exclusive_scan_d(double v, int lane, doub
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 2: acceptance test.  One wave per sequence; lane i < k owns draft position i, lane i <= k draw row i.
+// Launch 1, second role: acceptance test.  One wave per sequence; lane i < k owns draft position i, lane i <= k
+// draw row i.  The wave waits for the records of its 2k+1 rows (bounded; `stalled` when the wait ran out).
 // Returns, per lane, whether draw row `lane` of the sequence needs a draw.
-__device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int lane) {
-    const int k = a.k, K1 = a.k + 1, P = a.partials_per_row;
+__device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int lane, bool &stalled) {
+    const int k = a.k, K1 = a.k + 1, P = a.nsplit;
     const bool is_pos = lane < k;
     const double scale = (double)a.scale;
 
@@ -107,6 +108,8 @@ __device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int
             zqd = load_logit(a.draft_logits, a.dtype, ((int64_t)b * k + lane) * a.draft_stride + d);
         }
     }
+    const float u_acc = is_pos ? a.u_accept[(int64_t)b * k + lane] : 0.f;
+    const float u_drw = (lane < K1) ? a.u_draw[(int64_t)b * K1 + lane] : 0.f;
     int G = 1;
     while (2 * G * K1 <= kWaveSize) G *= 2;
     const int grow = lane / G, gs = lane & (G - 1);
@@ -115,18 +118,23 @@ __device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int
     float gm;
     int gt;
     double gS;
-    combine_row_partials(a.partials + ((int64_t)b * K1 + (grow < K1 ? grow : 0)) * P, P, G, gs, scale, gm, gt, gS);
+    const int64_t prow = (int64_t)b * K1 + (grow < K1 ? grow : 0);
+    bool ok = acquire_row_stats_any(a.records + prow * P, (uint64_t)prow * (uint64_t)P, P, G, gs, grow < K1, scale, a.reader_nonce,
+                                    a.spin_limit, gm, gt, gS);
     const float mp = from_lane_f(gm, src);
     const int tp = from_lane_i(gt, src);
     const double Sp = from_lane_d(gS, src);
     float mq = 0.f;
     double Sq = 1.0;
     if (k > 0) {
-        const int64_t qrow0 = (int64_t)a.B * K1 + (int64_t)b * k;   // draft rows follow the target rows
-        combine_row_partials(a.partials + (qrow0 + (grow < k ? grow : 0)) * P, P, G, gs, scale, gm, gt, gS);
+        const int64_t qrow = (int64_t)a.B * K1 + (int64_t)b * k + (grow < k ? grow : 0);   // draft rows follow the target rows
+        ok = acquire_row_stats_any(a.records + qrow * P, (uint64_t)qrow * (uint64_t)P, P, G, gs, grow < k, scale, a.reader_nonce,
+                                   a.spin_limit, gm, gt, gS) && ok;
         mq = from_lane_f(gm, src);
         Sq = from_lane_d(gS, src);
     }
+    stalled = !ok;
+    if (stalled) return false;
 
     bool rejected = false;
     if (is_pos) {
@@ -136,7 +144,7 @@ __device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int
             pd = exp2(((double)zpd - (double)mp) * scale) / Sp;
             qd = exp2(((double)zqd - (double)mq) * scale) / Sq;
             alpha = (qd <= 0.0) ? 1.0 : fmin(1.0, pd / qd);
-            rejected = (double)a.u_accept[(int64_t)b * k + lane] > alpha;
+            rejected = (double)u_acc > alpha;
         }
         const int64_t o = (int64_t)b * k + lane;
         if (a.alpha) a.alpha[o] = (float)alpha;
@@ -157,7 +165,7 @@ __device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int
             r.cq = mq * a.scale;
             r.fq = (float)(exp2((double)r.cq - (double)mq * scale) / Sq);
         }
-        r.u = a.u_draw[(int64_t)b * K1 + lane];
+        r.u = u_drw;
         r.pad = 0.f;
         a.rows[(int64_t)b * K1 + lane] = r;
         return r.need != 0;
@@ -165,25 +173,70 @@ __device__ __forceinline__ bool decide_sequence(const SampledArgs &a, int b, int
     return false;
 }
 
-__global__ __launch_bounds__(kApplyThreads) void sampled_decide_kernel(SampledArgs a) {
+// nothing of this sequence is drawn, and the last launch's sequence wave reports it as stalled
+__device__ __forceinline__ void mark_sequence_stalled(const SampledArgs &a, int b, int lane) {
+    const int K1 = a.k + 1;
+    if (lane < K1) {
+        DrawRow r = {(lane == a.k) ? 2 : 0, 0, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        a.rows[(int64_t)b * K1 + lane] = r;
+    }
+}
+
+// Launch 1: workgroups [0, n_stream_wgs) stream the 2k+1 rows of every sequence (target rows first, then draft
+// rows) and leave one record each; the workgroups after them take four sequences each, wait for their rows'
+// records and run the acceptance test, as the greedy step's single launch does with its sequence logic.  The rows
+// that need a draw go on a list (order immaterial), so that the second streaming pass has work for them only:
+// one LDS add per wave, one global add per workgroup.  The list's length is zeroed by the first workgroup of the
+// launch, which then says so in the list's control head; a workgroup adds to it only after seeing that.
+template <int DT>
+__global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void sampled_stream_kernel(StreamSource src, int V, SampledArgs a) {
+    __shared__ RowPartial wave_out[kStreamWaves];
     __shared__ unsigned int blk_count, blk_base;
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int b = blockIdx.x * kFinishWaves + (threadIdx.x >> 6);
-    if (threadIdx.x == 0) blk_count = 0;
+    const int wave = threadIdx.x >> 6;
+    if ((int)blockIdx.x < a.n_stream_wgs) {
+        const int row = blockIdx.x / a.nsplit;
+        const int split = share_of_workgroup((int)blockIdx.x - row * a.nsplit, row, a.nsplit);
+        if (blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.list_ctrl, step_ready_value(a.nonce));
+        const char *rowp = (row < src.rows0) ? src.base0 + (int64_t)row * src.pitch0
+                                             : src.base1 + (int64_t)(row - src.rows0) * src.pitch1;
+        const RowPartial out = stream_row_share<DT>(rowp, V, a.nsplit, split, wave, lane, src.scale);
+        publish_workgroup_share(wave_out, out, wave, lane, a.records, (uint64_t)row * a.nsplit + split, a.nonce);
+        return;
+    }
+    const int b = ((int)blockIdx.x - a.n_stream_wgs) * kStreamWaves + wave;
+    uint64_t ready_seen = 0;
+    if (threadIdx.x == 0) {
+        ready_seen = xwg_load64(&a.list_ctrl->ready);    // asked for early, looked at late
+        blk_count = 0;
+        blk_base = kNone;
+    }
     __syncthreads();
-    bool need = false;
-    if (b < a.B) need = decide_sequence(a, b, lane);      // wave-uniform: a wave takes a sequence or none
-    // the rows that need a draw go on a list (order immaterial), so that the second streaming pass launches
-    // work for them only: one LDS add per wave, one global add per workgroup
+    bool need = false, stalled = false;
+    if (b < a.B) need = decide_sequence(a, b, lane, stalled);      // wave-uniform: a wave takes a sequence or none
     const uint64_t mask = __builtin_amdgcn_ballot_w64(need);
     unsigned int off = 0;
     if (lane == 0 && mask) off = atomicAdd(&blk_count, (unsigned int)__builtin_popcountll(mask));
     off = __builtin_amdgcn_readfirstlane(off);
     __syncthreads();
-    if (threadIdx.x == 0 && blk_count) blk_base = atomicAdd(a.work_count, blk_count);
+    if (threadIdx.x == 0 && blk_count) {
+        const uint64_t ready_value = step_ready_value(a.reader_nonce);
+        bool good = true;
+        for (uint32_t spin = 0; ready_seen != ready_value; ++spin) {
+            if (spin >= a.spin_limit) { good = false; break; }
+            __builtin_amdgcn_s_sleep(kSpinSleep);
+            ready_seen = xwg_load64(&a.list_ctrl->ready);
+        }
+        if (good) blk_base = __hip_atomic_fetch_add(&a.list_ctrl->arrivals, blk_count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     __syncthreads();
-    if (need)
+    const bool listed = blk_base != (unsigned int)kNone;
+    if (need && listed)
         a.work_rows[blk_base + off + (unsigned int)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = b * (a.k + 1) + lane;
+    if (b < a.B && (stalled || (mask && !listed))) {     // wave-uniform
+        mark_sequence_stalled(a, b, lane);
+        if (lane == 0 && a.status != nullptr) atomicAdd(&a.status[CSD_STATUS_STALLED], 1u);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -193,14 +246,16 @@ template <int DT>
 __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
     using C = Chunk<DT>;
     const int groups = (a.nseg + kSegBlockWaves * kSegsPerWave - 1) / (kSegBlockWaves * kSegsPerWave);
-    const unsigned int items = *a.work_count * (unsigned int)groups;
+    const unsigned int items = a.list_ctrl->arrivals * (unsigned int)groups;
+    if (blockIdx.x == 0 && threadIdx.x == 0) xwg_store64(&a.list_ctrl->ready, 0ull);   // a replay of this step waits for its own
     // the row of the NEXT item is fetched while this one is streamed: otherwise every item would begin with a
     // dependent load (three microseconds on a busy chip) before its own loads could be issued
     int j_next = (blockIdx.x < items) ? a.work_rows[blockIdx.x / groups] : 0;
     for (unsigned int item = blockIdx.x; item < items; item += gridDim.x) {
         const int j = j_next;
         if (item + gridDim.x < items) j_next = a.work_rows[(item + gridDim.x) / groups];
-        const int group = (int)(item % groups);
+        // rotated by the list position for the reason share_of_workgroup gives: the last group of a row is the short one
+        const int group = share_of_workgroup((int)(item % groups), (int)(item / groups), groups);
         const DrawRow r = a.rows[j];
         const int lane = threadIdx.x & (kWaveSize - 1);
         const int wave = threadIdx.x >> 6;
@@ -257,17 +312,28 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
     const int K1 = a.k + 1;
     const int b = (int)(j / K1), i = (int)(j - (int64_t)b * K1);
     int32_t *out = (i < a.k) ? &a.tstar[(int64_t)b * a.k + i] : &a.bonus[b];
-    const DrawRow r = a.rows[j];
-    if (!r.need) {
-        if (lane == 0) *out = -1;
-        return -1;
-    }
-    // ---- which segment: lane l owns segments [l*per, (l+1)*per)
+    // ---- which segment: lane l owns segments [l*per, (l+1)*per).  Up to four per lane (every vocabulary below
+    // half a million bf16 logits) are fetched together with the row's constants, before it is known whether the
+    // row needs a draw at all: one memory round trip, not two, and no second read of them below.
     const float *seg = a.segsum + j * a.nseg;
     const int per = (a.nseg + kWaveSize - 1) / kWaveSize;
     const int s0 = lane * per;
+    constexpr int kSegRegs = 4;
+    float sv[kSegRegs];
+#pragma unroll
+    for (int u = 0; u < kSegRegs; ++u) sv[u] = (per <= kSegRegs && u < per && s0 + u < a.nseg) ? seg[s0 + u] : 0.f;
+    const DrawRow r = a.rows[j];
+    if (r.need != 1) {
+        if (lane == 0) *out = -1;
+        return -1;
+    }
     double local = 0.0;
-    for (int s = s0; s < s0 + per && s < a.nseg; ++s) local += (double)seg[s];
+    if (per <= kSegRegs) {
+#pragma unroll
+        for (int u = 0; u < kSegRegs; ++u) local += (double)sv[u];          // absent ones are zero
+    } else {
+        for (int s = s0; s < s0 + per && s < a.nseg; ++s) local += (double)seg[s];
+    }
     double R;
     const double before = wave_exclusive_scan_d(local, lane, R);
     int result = -1;
@@ -275,14 +341,19 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
         const double target = (double)r.u * R;
         int found = kNone, lastpos = -1;
         double base = 0.0, acc = before;
-        for (int s = s0; s < s0 + per && s < a.nseg; ++s) {
-            const double v = (double)seg[s];
+        auto visit = [&](int s, double v) {
             if (v > 0.0) lastpos = s;
             if (found == kNone && v > 0.0 && acc + v > target) {    // a segment without mass is never chosen
                 found = s;
                 base = acc;
             }
             acc += v;
+        };
+        if (per <= kSegRegs) {
+#pragma unroll
+            for (int u = 0; u < kSegRegs; ++u) visit(s0 + u, (double)sv[u]);
+        } else {
+            for (int s = s0; s < s0 + per && s < a.nseg; ++s) visit(s, (double)seg[s]);
         }
         int sstar = wave_allreduce_i(found, MinI());
         if (sstar == kNone) {                              // rounding at the very end of the row: last segment with mass
@@ -355,7 +426,8 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
 // ---------------------------------------------------------------------------------------------------
 // Launch 4, second role: the loop itself.  One wave per sequence; it waits for the draws of its k+1 rows, which
 // the first role's waves of the same launch publish.
-__device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters, bool &stalled) {
+__device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters, bool &stalled,
+                                                       bool &stalled_before) {
     const int k = a.k, K1 = a.k + 1;
     const bool is_pos = lane < k;
     int d = -1;
@@ -369,7 +441,15 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
         valid = st & 2;
         zpd = a.pos_zpd[o];
     }
-    const int fallback = a.rows[(int64_t)b * K1 + (lane < K1 ? lane : 0)].fallback;
+    const DrawRow *mine_row = &a.rows[(int64_t)b * K1 + (lane < K1 ? lane : 0)];
+    const int fallback = mine_row->fallback;
+    stalled_before = from_lane_i(mine_row->need, k) == 2;     // the first launch gave this sequence up (and counted it)
+    Divergence out;
+    out.counted = false;
+    out.key = 0;
+    out.probe = OcmProbe{0, 0, false, false};
+    stalled = stalled_before;
+    if (stalled_before) return out;
     // the draws of this sequence's rows: lane i takes row i's
     int t = -1;
     bool got = true;
@@ -380,10 +460,6 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
         t = (int)(uint32_t)v;
     }
     stalled = __builtin_amdgcn_ballot_w64(!got) != 0ull;
-    Divergence out;
-    out.counted = false;
-    out.key = 0;
-    out.probe = OcmProbe{0, 0, false, false};
     if (stalled) return out;
     const int bonus = from_lane_i(t, k);
     if (is_pos && rejected && valid) zpt = load_logit(a.target, a.dtype, ((int64_t)b * K1 + lane) * a.target_stride + t);
@@ -473,12 +549,11 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
     dv.key = 0;
     dv.probe = OcmProbe{0, 0, false, false};
     if (b < a.B) {                                         // wave-uniform: a wave takes a sequence or none
-        bool stalled = false;
-        dv = sampled_sequence(a, b, lane, counters, stalled);
-        if (stalled && lane == 0) {                        // the draws never came: say so, and report nothing as accepted
-            a.accept_len[b] = 0;
-            a.next_token[b] = -1;
-            atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
+        bool stalled = false, stalled_before = false;
+        dv = sampled_sequence(a, b, lane, counters, stalled, stalled_before);
+        if (stalled) {                                     // the draws never came: say so, and report nothing as accepted
+            report_stalled_sequence(a.accept_len, a.next_token, a.pos_flags, a.rej_log, b, a.k, lane);
+            if (lane == 0 && !stalled_before) atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
         }
     }
     sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)n_seq_wgs,
@@ -493,22 +568,24 @@ int sampled_segments(int V, int dtype) {
     return (nchunks + kSegChunks - 1) / kSegChunks;
 }
 
-hipError_t launch_sampled_tail(const SampledArgs &a, hipStream_t stream) {
+hipError_t launch_sampled_step(const StreamSource &src, const SampledArgs &a, hipStream_t stream) {
     if (a.B == 0) return hipSuccess;
     const int K1 = a.k + 1;
-    const dim3 seq_grid((unsigned)((a.B + kFinishWaves - 1) / kFinishWaves)), seq_block(kApplyThreads);
-    hipLaunchKernelGGL(sampled_decide_kernel, seq_grid, seq_block, 0, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const dim3 first_grid((unsigned)(a.n_stream_wgs + (a.B + kStreamWaves - 1) / kStreamWaves)), first_block(kStreamWaves * kWaveSize);
     const int per_block = kSegBlockWaves * kSegsPerWave;
     const int64_t max_items = (int64_t)a.B * K1 * ((a.nseg + per_block - 1) / per_block);
     const dim3 seg_grid((unsigned)(max_items < kSegGrid ? max_items : kSegGrid));
     const dim3 tail_grid((unsigned)(a.n_loc_wgs + (a.B + kSegBlockWaves - 1) / kSegBlockWaves)), tail_block(kSegBlockWaves * kWaveSize);
+    hipError_t e;
     if (a.dtype == CSD_DTYPE_F32) {
+        hipLaunchKernelGGL(sampled_stream_kernel<CSD_DTYPE_F32>, first_grid, first_block, 0, stream, src, a.V, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_F32>, tail_grid, tail_block, 0, stream, a);
     } else {
+        hipLaunchKernelGGL(sampled_stream_kernel<CSD_DTYPE_BF16>, first_grid, first_block, 0, stream, src, a.V, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_BF16>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_BF16>, tail_grid, tail_block, 0, stream, a);

@@ -40,152 +40,10 @@
 //                        are acknowledged before the workgroup barrier that precedes the ticket, itself an
 //                        agent-scope atomic add.  (A release/acquire fence pair would do the same job by writing
 //                        back and invalidating a whole L2 per wave, which measured ten times the streaming pass.)
-#include "csd_device.h"
+#include "csd_stream.h"
 
 namespace csd {
 namespace {
-
-constexpr float kLog2e = CSD_LOG2E_F32;
-constexpr double kLog2eD = (double)CSD_LOG2E_F32;
-constexpr float kRescaleGapLog2 = 28.8f;   // reference stays within this of the maximum, in exponent (log2) units:
-                                           // 20 logits at temperature 1; below 32 keeps the exponent's ulp at 2^-19 or finer
-constexpr int kNoIter = 0x7fffffff;
-constexpr int kRemIter = 1 << 30;      // best_it values at or above this index the remainder loop
-
-// ---------------------------------------------------------------------------------------------------
-// Phase 1: this wave's share of one row -> one RowPartial (returned in lane-uniform registers).
-template <int DT>
-__device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ rowp, int V, int nsplit, int split,
-                                                       int wave, int lane, float scale) {
-    using C = Chunk<DT>;
-    constexpr int E = C::E;
-    constexpr int W = kStreamWaves;
-    constexpr int U = kStreamUnroll;
-    constexpr int WL = W * kWaveSize;              // chunks one load instruction of the workgroup covers
-
-    const int nfull = V / E;                       // whole 16-byte chunks of the row
-    const int tail = V - nfull * E;                // logits in the ragged last chunk
-    const int nchunks = nfull + (tail ? 1 : 0);
-    const int ntiles_row = nfull / kTileChunks;    // whole tiles of whole chunks
-    const int rem0 = ntiles_row * kTileChunks;     // first chunk of the remainder
-    // This workgroup's tiles: a contiguous run of the row (the first `extra` workgroups take one tile more); the
-    // last workgroup, which has the fewest tiles, also takes the remainder.
-    const int base_tiles = ntiles_row / nsplit, extra = ntiles_row - base_tiles * nsplit;
-    const int tile0 = split * base_tiles + (split < extra ? split : extra);
-    const int ntiles = base_tiles + (split < extra ? 1 : 0);
-    const bool has_rem = (split == nsplit - 1) && (rem0 < nchunks);
-
-    float rm = -INFINITY;      // running max of this lane
-    int best_it = kNoIter;     // iteration that first reached rm ...
-    u32x4 best_q = {0u, 0u, 0u, 0u};   // ... and the chunk read there
-    float s[E];
-#pragma unroll
-    for (int j = 0; j < E; ++j) s[j] = 0.f;
-    float c = 0.f;             // wave-uniform reference exponent (log2 units)
-    float mth = -INFINITY;     // rescale when a lane maximum exceeds this
-    const float gap = kRescaleGapLog2 / scale;   // the same distance in logit units
-    const int lane_chunk0 = wave * kWaveSize + lane;
-
-    auto rescale = [&]() {
-        const float wm = wave_allreduce_f(rm, MaxF());
-        const float cn = wm * scale;
-        const float sc = __builtin_amdgcn_exp2f(c - cn);
-#pragma unroll
-        for (int j = 0; j < E; ++j) s[j] = (s[j] == 0.f) ? 0.f : s[j] * sc;
-        c = cn;
-        mth = wm + gap;
-    };
-
-    // ---- whole tiles: U independent non-temporal 16-byte loads per lane.
-    // Local tile t is row tile tile0 + t; its chunk for (u, this lane) is
-    //     (tile0 + t) * kTileChunks + u*WL + lane_chunk0   < ntiles_row * kTileChunks <= nfull.
-    const u32x4 *p = (const u32x4 *)rowp + (size_t)tile0 * kTileChunks + lane_chunk0;
-    for (int t = 0; t < ntiles; ++t) {
-        u32x4 q[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(p + u * WL);
-        p += kTileChunks;
-
-        float x[U][E];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            C::unpack(q[u], x[u]);
-            const float cm = chunk_max<E>(x[u]);
-            const bool up = cm > rm;
-            best_it = up ? (t * U + u) : best_it;
-            best_q.x = up ? q[u].x : best_q.x;
-            best_q.y = up ? q[u].y : best_q.y;
-            best_q.z = up ? q[u].z : best_q.z;
-            best_q.w = up ? q[u].w : best_q.w;
-            rm = __builtin_fmaxf(rm, cm);
-        }
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(rm > mth) != 0, 0)) rescale();
-        const float nc = -c;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][j], scale, nc));
-        }
-    }
-
-    // ---- remainder of the row (one workgroup per row): one guarded chunk per lane per iteration;
-    // slots past V are filled with -inf, the ragged chunk is read element by element.
-    if (has_rem) {
-        for (int it = 0; rem0 + it * WL < nchunks; ++it) {
-            const int ch = rem0 + it * WL + lane_chunk0;
-            u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
-            if (ch < nfull) {
-                q = ((const u32x4 *)rowp)[ch];
-            } else if (ch == nfull) {
-                q = C::load_ragged(rowp, nfull * E, tail);
-            }
-            float x[E];
-            C::unpack(q, x);
-            const float cm = chunk_max<E>(x);
-            const bool up = cm > rm;
-            best_it = up ? (kRemIter + it) : best_it;
-            best_q.x = up ? q.x : best_q.x;
-            best_q.y = up ? q.y : best_q.y;
-            best_q.z = up ? q.z : best_q.z;
-            best_q.w = up ? q.w : best_q.w;
-            rm = __builtin_fmaxf(rm, cm);
-            if (__builtin_amdgcn_ballot_w64(rm > mth) != 0) rescale();
-            const float nc = -c;
-#pragma unroll
-            for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], scale, nc));
-        }
-    }
-
-    // ---- wave result
-    float sl = s[0];
-#pragma unroll
-    for (int j = 1; j < E; ++j) sl += s[j];
-    const float ws = wave_allreduce_f(sl, AddF());
-    const float wm = wave_allreduce_f(rm, MaxF());
-    // Lanes that hold the wave maximum name the lowest token id at which they saw it: the first element
-    // of their saved chunk equal to it (float compare: -0 == +0).  The wave takes the smallest.
-    int my_idx = kNoIter;
-    if (best_it != kNoIter && rm == wm) {
-        const int chunk = (best_it >= kRemIter)
-                              ? rem0 + (best_it - kRemIter) * WL + lane_chunk0
-                              : (tile0 + best_it / U) * kTileChunks + (best_it % U) * WL + lane_chunk0;
-        float x[E];
-        C::unpack(best_q, x);
-        int j0 = E - 1;
-#pragma unroll
-        for (int j = E - 1; j >= 0; --j) j0 = (x[j] == wm) ? j : j0;
-        my_idx = chunk * E + j0;
-    }
-    int idx = wave_allreduce_i(my_idx, MinI());
-    // a share without any finite value reports the first token it covers (token 0 if it covers nothing)
-    if (idx == kNoIter) idx = ((ntiles > 0) ? tile0 * kTileChunks : (has_rem ? rem0 : 0)) * E;
-    RowPartial out;
-    out.m = wm;
-    out.cref = c;
-    out.s = ws;
-    out.idx = idx;
-    return out;
-}
 
 // ---------------------------------------------------------------------------------------------------
 // Phase 2: one wave, one sequence (all 64 lanes active on entry).  Lane i < k owns draft position i.
@@ -346,7 +204,7 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kerne
                                                                                   RowPartial *__restrict__ partials,
                                                                                   uint32_t *batch_ticket) {
     const int row = blockIdx.x / nsplit;
-    const int split = blockIdx.x - row * nsplit;
+    const int split = share_of_workgroup((int)blockIdx.x - row * nsplit, row, nsplit);
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     // the later kernels' two counters (the batch ticket and, on the sampled path, the length of the list of
@@ -402,76 +260,6 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 // on one record per sequence before polling all (no gain once records are one per workgroup); per-wave records
 // (three rounds of loads at k = 8).
 
-// the check word of a record: a hash of its two data words, of the call's number and of the record's index
-__device__ __forceinline__ uint64_t record_check(uint64_t w0, uint64_t w1, uint64_t nonce, uint64_t rec) {
-    return mix64(w0 + mix64(w1 ^ (nonce + rec * 0x9E3779B97F4A7C15ull))) | 1ull;   // never zero: a zeroed record does not pass
-}
-__device__ __forceinline__ void publish_record(StepRecord *r, uint64_t nonce, uint64_t rec, const RowPartial &p) {
-    const uint64_t w0 = (uint64_t)__float_as_uint(p.m) | ((uint64_t)__float_as_uint(p.cref) << 32);
-    const uint64_t w1 = (uint64_t)__float_as_uint(p.s) | ((uint64_t)(uint32_t)p.idx << 32);
-    xwg_store64(&r->w0, w0);
-    xwg_store64(&r->w1, w1);
-    xwg_store64(&r->check, record_check(w0, w1, nonce, rec));
-}
-
-// Records j = gs + (u0 + u)*G, u < N, of one row: loaded until they pass, all N of a round in flight together
-// (one memory round trip when they are all there).  `want` says which of them this lane needs; passing ones
-// are decoded into q and their check word zeroed.  Returns false when the wait ran out.  Called by all lanes
-// of the wave together.
-template <int N>
-__device__ __forceinline__ bool acquire_records(StepRecord *row_rec, uint64_t rec0, int G, int gs, int u0, uint32_t want,
-                                                uint64_t nonce, uint32_t spin_limit, RowPartial (&q)[N]) {
-    uint32_t pend = want;
-    for (uint32_t spin = 0;; ++spin) {
-        uint64_t w0[N], w1[N], ck[N];
-#pragma unroll
-        for (int u = 0; u < N; ++u) {
-            if ((pend >> u) & 1u) {
-                const StepRecord *r = row_rec + gs + (u0 + u) * G;
-                w0[u] = xwg_load64(&r->w0);
-                w1[u] = xwg_load64(&r->w1);
-                ck[u] = xwg_load64(&r->check);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < N; ++u) {
-            if ((pend >> u) & 1u) {
-                const uint64_t j = (uint64_t)(gs + (u0 + u) * G);
-                if (ck[u] == record_check(w0[u], w1[u], nonce, rec0 + j)) {
-                    q[u].m = __uint_as_float((uint32_t)w0[u]);
-                    q[u].cref = __uint_as_float((uint32_t)(w0[u] >> 32));
-                    q[u].s = __uint_as_float((uint32_t)w1[u]);
-                    q[u].idx = (int32_t)(uint32_t)(w1[u] >> 32);
-                    xwg_store64(&row_rec[gs + (u0 + u) * G].check, 0ull);
-                    pend &= ~(1u << u);
-                }
-            }
-        }
-        if (__builtin_amdgcn_ballot_w64(pend != 0u) == 0ull) return true;
-        if (spin >= spin_limit) return false;
-        __builtin_amdgcn_s_sleep(kSpinSleep);
-    }
-}
-
-// All records of this lane's share of its row -> (m, t*, S) of the row, in the first lane of its group, with the
-// arithmetic of the two-launch combine, in its order.
-template <int NB>
-__device__ __forceinline__ bool acquire_row_stats(StepRecord *row_rec, uint64_t rec0, int P, int G, int gs, bool active,
-                                                  uint64_t nonce, uint32_t spin_limit, float &gm, int &t, double &S) {
-    RowPartial q[NB];
-    uint32_t want = 0;
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-        q[u] = empty_partial();
-        if (active && gs + u * G < P) want |= 1u << u;
-    }
-    const bool ok = acquire_records<NB>(row_rec, rec0, G, gs, 0, want, nonce, spin_limit, q);
-    gm = -INFINITY;
-    t = 0x7fffffff;
-    S = 0.0;
-    combine_partials_in_registers<NB>(q, G, kLog2eD, gm, t, S);
-    return ok;
-}
 
 __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCounters &counters, int *verdict) {
     const int lane = threadIdx.x & (kWaveSize - 1);
@@ -498,47 +286,10 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
         const int64_t prow = (int64_t)b * K1 + (active ? grow : 0);
         StepRecord *row_rec = a.records + prow * P;
         const uint64_t rec0 = (uint64_t)prow * (uint64_t)P;
-        const int per_lane = (P + G - 1) / G;        // wave-uniform
         float gm;
         int t;
         double S;
-        bool ok;
-        if (per_lane <= 4) {                         // every benchmark shape: one round trip for the whole sequence
-            ok = acquire_row_stats<4>(row_rec, rec0, P, G, gs, active, a.reader_nonce, a.spin_limit, gm, t, S);
-        } else {
-            // many partials per lane (a huge vocabulary under a small batch): wait for them four at a time, keeping
-            // the running maximum only, then take the sums in a second pass over the (now plainly readable) words
-            ok = true;
-            gm = -INFINITY;
-            t = 0x7fffffff;
-            S = 0.0;
-            for (int u0 = 0; u0 < per_lane; u0 += 4) {
-                RowPartial q4[4];
-                uint32_t want = 0;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    q4[u] = empty_partial();
-                    if (active && gs + (u0 + u) * G < P) want |= 1u << u;
-                }
-                if (__builtin_amdgcn_ballot_w64(want != 0u) != 0ull)
-                    ok = acquire_records<4>(row_rec, rec0, G, gs, u0, want, a.reader_nonce, a.spin_limit, q4) && ok;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (q4[u].m > gm || (q4[u].m == gm && q4[u].idx < t)) t = q4[u].idx;
-                    gm = fmaxf(gm, q4[u].m);
-                }
-            }
-            partials_max_merge(G, gm, t);
-            const double mref = (double)gm * kLog2eD;
-            if (active) {
-                for (int j = gs; j < P; j += G) {
-                    const uint64_t w0 = xwg_load64(&row_rec[j].w0), w1 = xwg_load64(&row_rec[j].w1);
-                    const float cref = __uint_as_float((uint32_t)(w0 >> 32)), sj = __uint_as_float((uint32_t)w1);
-                    if (sj != 0.f) S += (double)sj * (double)__builtin_amdgcn_exp2f((float)((double)cref - mref));
-                }
-            }
-            partials_sum_merge(G, S);
-        }
+        const bool ok = acquire_row_stats_any(row_rec, rec0, P, G, gs, active, kLog2eD, a.reader_nonce, a.spin_limit, gm, t, S);
         stalled = !ok;
         if (!stalled) {
             float rmax;
@@ -547,10 +298,9 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
             publish_row_stats(a, b, lane, G, gm, t, S, rmax, tstar, rS);
             if (a.update_here) dv = sequence_decide<true>(a, b, lane, dl, rmax, tstar, rS, counters);
             else dv = sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, counters);
-        } else if (lane == 0) {                      // the records never came: say so, and report nothing as accepted
-            a.accept_len[b] = 0;
-            a.next_token[b] = -1;
-            atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
+        } else {                                     // the records never came: say so, and report nothing as accepted
+            report_stalled_sequence(a.accept_len, a.next_token, a.pos_flags, a.rej_log, b, k, lane);
+            if (lane == 0) atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
         }
     }
 
@@ -569,39 +319,13 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void verify_step_kernel
         return;
     }
     const int row = blockIdx.x / nsplit;
-    const int split = blockIdx.x - row * nsplit;
+    const int split = share_of_workgroup((int)blockIdx.x - row * nsplit, row, nsplit);
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl, step_ready_value(a.nonce));
     const char *rowp = src.base0 + (int64_t)row * src.pitch0;
     const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
-    // The four waves of the workgroup (they sweep the same tiles and end together) leave ONE record: fewer records
-    // for the sequence waves to wait for and to read.  Same combine rule as between records; the sum is taken in
-    // double against the largest reference exponent and rounded to float once.
-    if (lane == 0) wave_out[wave] = out;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        RowPartial r = empty_partial();
-        r.idx = wave_out[0].idx;
-        float cmax = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kStreamWaves; ++w) {
-            const RowPartial q = wave_out[w];
-            if (q.m > r.m || (q.m == r.m && q.idx < r.idx)) r.idx = q.idx;
-            r.m = fmaxf(r.m, q.m);
-            if (q.s != 0.f) cmax = fmaxf(cmax, q.cref);
-        }
-        double sum = 0.0;
-#pragma unroll
-        for (int w = 0; w < kStreamWaves; ++w) {
-            const RowPartial q = wave_out[w];
-            if (q.s != 0.f) sum += (double)q.s * (double)__builtin_amdgcn_exp2f(q.cref - cmax);
-        }
-        r.cref = (sum != 0.0) ? cmax : 0.f;
-        r.s = (float)sum;
-        const uint64_t rec = (uint64_t)row * nsplit + split;
-        publish_record(a.records + rec, a.nonce, rec, r);
-    }
+    publish_workgroup_share(wave_out, out, wave, lane, a.records, (uint64_t)row * nsplit + split, a.nonce);
 }
 
 }  // namespace

@@ -13,7 +13,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(kWaves *kLanes, 4) void read_probe_kernel(const char *base, int64_t pitch, int64_t chunks_per_row,
                                                                       int nsplit, uint32_t *sink) {
-    const int row = blockIdx.x / nsplit, split = blockIdx.x - row * nsplit;
+    const int row = blockIdx.x / nsplit, place = (int)blockIdx.x - row * nsplit,
+              split = (nsplit & 1) ? place : (place + row) % nsplit;   // rotated by the row as the product deals its shares
     const int64_t ntiles_row = chunks_per_row / kTileChunks;
     const int64_t base_tiles = ntiles_row / nsplit, extra = ntiles_row - base_tiles * nsplit;
     const int64_t tile0 = split * base_tiles + (split < extra ? split : extra);
