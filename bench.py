@@ -428,7 +428,7 @@ def main() -> int:
     if args.ingest_pmc:
         if args.path == "sampled":
             return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name + "+sampled",
-                              (STREAM_KERNEL, "residual_segments_kernel"))
+                              ("sampled_stream_kernel", "residual_segments_kernel"))
         return ingest_pmc(args.ingest_pmc[0], args.ingest_pmc[1], cfg.name, (STEP_KERNEL,))
 
     import torch

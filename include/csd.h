@@ -195,10 +195,11 @@ int csd_verify_static(const void *logits, int dtype, int64_t row_stride, const i
  * A draw whose u * mass falls within rounding of a boundary of the running sum may land on either
  * neighbour; a residual without any mass reports the target row's argmax.  An id outside [0,V) ends
  * the loop uncounted with the row's argmax as the emitted token.
- * Four launches: the streaming pass over all 2k+1 rows per sequence, the acceptance test, a second
- * streaming pass over the rows that need a draw (target and draft row side by side), and one launch in which
- * waves invert the running sums while the sequence waves of the same grid wait for their draws and then run
- * the loop with the memory updates (bounded waits, see CSD_STATUS_STALLED).
+ * Three launches: the streaming pass over all 2k+1 rows per sequence, with the acceptance test in waves at the
+ * end of the same grid; a second streaming pass over the rows that need a draw (target and draft row side by
+ * side); and one launch in which waves invert the running sums while the sequence waves of the same grid wait
+ * for their draws and then run the loop with the memory updates.  Waits inside a launch are bounded, see
+ * CSD_STATUS_STALLED.
  */
 size_t csd_verify_sampled_workspace_bytes(int B, int k, int V, int dtype);
 int csd_verify_sampled(const void *target_logits, const void *draft_logits, int dtype, int64_t target_row_stride,

@@ -8,19 +8,26 @@
 //          count the pair, then keep x~ (rescued) or stop and emit t*
 //   all kept: emit a draw from p_{k+1}.
 //
-// Four launches on the caller's stream:
-//   1. row_partials_kernel (csd_verify.hip) over the B(k+1) target rows and the Bk draft rows in one grid,
-//      with the exponent scale log2(e)/T: maxima and normalisers at temperature T.        [HBM-bound]
-//   2. sampled_decide_kernel, one wave per sequence: combine the partials, p(x~), q(x~), alpha, the
-//      acceptance test; leaves for every "draw row" (a rejected position, or the bonus row) the constants
-//      that turn a logit into a probability, and a list of the rows that need a draw.
-//   3. residual_segments_kernel, a fixed grid walking that list: streams the target row and the draft row
-//      side by side and leaves the residual mass of every segment of 256 chunks.          [HBM-bound]
-//   4. sampled_tail_kernel.  First role, one wave per draw row: scans the segment masses in double, finds the
+// Three launches on the caller's stream:
+//   1. sampled_stream_kernel.  First role: the streaming pass (csd_stream.h) over the B(k+1) target rows and the
+//      Bk draft rows in one grid, with the exponent scale log2(e)/T: maxima and normalisers at temperature T,
+//      one record per workgroup.                                                           [HBM-bound]
+//      Second role (workgroups at the end of the grid), one wave per sequence: waits for the records of its
+//      rows, then p(x~), q(x~), alpha, the acceptance test; leaves for every "draw row" (a rejected position,
+//      or the bonus row) the constants that turn a logit into a probability, and a list of the rows that need
+//      a draw.
+//   2. residual_segments_kernel, one workgroup per (row of that list, group of segments): streams the target
+//      row and the draft row side by side and leaves the residual mass of every segment of 256 chunks.
+//                                                                                          [HBM-bound]
+//   3. sampled_tail_kernel.  First role, one wave per draw row: scans the segment masses in double, finds the
 //      segment that holds u*R, re-reads that one segment, walks to the token and publishes the draw.  Second
 //      role (workgroups at the end of the grid), one wave per sequence: waits for the draws of its rows, then
 //      lookup, gate, accepted-prefix scan, emitted token, log, and the step's updates after a barrier of the
 //      sequence workgroups (the same tail as the greedy step's single launch).
+// Measured at 256 sequences, k = 4, 256000 bf16 logits, T = 1 (about 630 draw rows): 174 + 76 + 16 microseconds.
+// In the last launch a draw is published 5 us after the launch began at the median and 7.4 at the latest (0.4
+// row constants and segment masses, 0.6 choosing the segment, 2.6 re-reading it, 1.2 - 2 finding the token), the
+// sequence waves have their draws at 8, have run the loop at 9.5, and the updates are out at 13.5.
 // Positions whose acceptance test fails are all drawn (the draws do not depend on each other), although
 // the loop may stop before it reaches some of them; so is the bonus token of every sequence.
 #include "csd_stream.h"
@@ -31,8 +38,9 @@ namespace {
 constexpr int kSegLoads = 4;                          // 16-byte loads per lane and segment
 constexpr int kSegChunks = kWaveSize * kSegLoads;     // chunks per segment (one wave sweeps a segment)
 constexpr int kSegsPerWave = 2;                       // segments one wave takes per item: one round of loads
-constexpr int kSegBlockWaves = 4;
-constexpr int kSegGrid = 4096;                        // workgroups of the segment kernel (it walks a list)
+constexpr int kSegBlockWaves = 4;                      // waves per workgroup of the last launch
+constexpr int kSegItemWaves = 4;                       // waves per workgroup of the segment kernel: one item
+constexpr int kSegGrid = 1 << 22;                     // most workgroups of the segment kernel
 constexpr int kNone = 0x7fffffff;
 
 // probability of one logit from the row constants: 2^(z*scale - c) * f.  Separate roundings (no
@@ -240,20 +248,18 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void sampled_stream_ker
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 3: residual mass per segment, for the rows on the list only.  A fixed grid of workgroups walks the
-// items (row of the list, group of segments): no workgroup is launched for a row that needs nothing.
+// Launch 2: residual mass per segment, for the rows on the list only.  One workgroup per item (row of the list,
+// group of segments); the grid is sized for every row needing a draw (up to kSegGrid workgroups, which then take
+// several items each) and the workgroups beyond the list's end leave at once.  (A fixed grid of 4096 workgroups walking the items measured 1.5 % slower on the whole step,
+// workgroups of 1, 2 and 8 waves 1 - 2.5 % slower than these 4.)
 template <int DT>
-__global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
+__global__ __launch_bounds__(kSegItemWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
     using C = Chunk<DT>;
-    const int groups = (a.nseg + kSegBlockWaves * kSegsPerWave - 1) / (kSegBlockWaves * kSegsPerWave);
+    const int groups = (a.nseg + kSegItemWaves * kSegsPerWave - 1) / (kSegItemWaves * kSegsPerWave);
     const unsigned int items = a.list_ctrl->arrivals * (unsigned int)groups;
     if (blockIdx.x == 0 && threadIdx.x == 0) xwg_store64(&a.list_ctrl->ready, 0ull);   // a replay of this step waits for its own
-    // the row of the NEXT item is fetched while this one is streamed: otherwise every item would begin with a
-    // dependent load (three microseconds on a busy chip) before its own loads could be issued
-    int j_next = (blockIdx.x < items) ? a.work_rows[blockIdx.x / groups] : 0;
-    for (unsigned int item = blockIdx.x; item < items; item += gridDim.x) {
-        const int j = j_next;
-        if (item + gridDim.x < items) j_next = a.work_rows[(item + gridDim.x) / groups];
+    for (unsigned int item = blockIdx.x; item < items; item += gridDim.x) {   // one turn, but for grids beyond kSegGrid
+        const int j = a.work_rows[item / groups];
         // rotated by the list position for the reason share_of_workgroup gives: the last group of a row is the short one
         const int group = share_of_workgroup((int)(item % groups), (int)(item / groups), groups);
         const DrawRow r = a.rows[j];
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
         const char *prow = (const char *)a.target + (int64_t)j * a.target_stride * esz;
         const char *qrow = use_q ? (const char *)a.draft_logits + ((int64_t)b * a.k + i) * a.draft_stride * esz : prow;
         const int nfull = a.V / C::E, tail = a.V - nfull * C::E;
-        const int seg0 = (group * kSegBlockWaves + wave) * kSegsPerWave;
+        const int seg0 = (group * kSegItemWaves + wave) * kSegsPerWave;
         // two segments at a time: all their loads (2 x kSegLoads per tensor) are issued before any arithmetic
         for (int s = seg0; s < seg0 + kSegsPerWave && s < a.nseg; s += 2) {
             constexpr int N = 2 * kSegLoads;
@@ -304,7 +310,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void residual_segments_k
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 4, first role: invert the running sum.  One wave per draw row j; returns the drawn token (-1 when the
+// Launch 3, first role: invert the running sum.  One wave per draw row j; returns the drawn token (-1 when the
 // row needs no draw) in every lane and writes it to the tstar / bonus output.
 template <int DT>
 __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int lane) {
@@ -379,33 +385,40 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
             cp[u] = load_chunk_guarded<DT>(prow, ch, nfull, tail);
             cq[u] = use_q ? load_chunk_guarded<DT>(qrow, ch, nfull, tail) : cp[u];
         }
+        // the four running sums (one per load) are independent: taken together, their shuffles overlap
+        float w[kSegLoads][C::E];
+        double lsum[kSegLoads], excl[kSegLoads], tot[kSegLoads];
+        int my_last[kSegLoads];
+#pragma unroll
+        for (int u = 0; u < kSegLoads; ++u) {
+            const int ch = sstar * kSegChunks + u * kWaveSize + lane;
+            weights_of<DT>(cp[u], cq[u], use_q, a.scale, r, w[u]);
+            lsum[u] = 0.0;
+            my_last[u] = -1;
+#pragma unroll
+            for (int e = 0; e < C::E; ++e) {
+                lsum[u] += (double)w[u][e];
+                if (w[u][e] > 0.f) my_last[u] = ch * C::E + e;
+            }
+            last_tok = my_last[u] > last_tok ? my_last[u] : last_tok;
+        }
+#pragma unroll
+        for (int u = 0; u < kSegLoads; ++u) excl[u] = wave_exclusive_scan_d(lsum[u], lane, tot[u]);
 #pragma unroll
         for (int u = 0; u < kSegLoads; ++u) {
             if (result >= 0) break;
             const int ch = sstar * kSegChunks + u * kWaveSize + lane;
-            float w[C::E];
-            weights_of<DT>(cp[u], cq[u], use_q, a.scale, r, w);
-            double lsum = 0.0;
-            int my_last = -1;
-#pragma unroll
-            for (int e = 0; e < C::E; ++e) {
-                lsum += (double)w[e];
-                if (w[e] > 0.f) my_last = ch * C::E + e;
-            }
-            last_tok = my_last > last_tok ? my_last : last_tok;
-            double tot;
-            const double excl = wave_exclusive_scan_d(lsum, lane, tot);
-            const uint64_t hit = __builtin_amdgcn_ballot_w64(lsum > 0.0 && excl + lsum > rem);   // only lanes holding mass
+            const uint64_t hit = __builtin_amdgcn_ballot_w64(lsum[u] > 0.0 && excl[u] + lsum[u] > rem);   // only lanes holding mass
             if (hit) {
                 const int L = (int)__builtin_ctzll(hit);
-                int tok = my_last;
+                int tok = my_last[u];
                 if (lane == L) {
-                    double c = excl;
+                    double c = excl[u];
                     bool done = false;
 #pragma unroll
                     for (int e = 0; e < C::E; ++e) {
-                        c += (double)w[e];
-                        if (!done && w[e] > 0.f && c > rem) {      // never a token outside the residual's support
+                        c += (double)w[u][e];
+                        if (!done && w[u][e] > 0.f && c > rem) {   // never a token outside the residual's support
                             tok = ch * C::E + e;
                             done = true;
                         }
@@ -413,7 +426,7 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
                 }
                 result = from_lane_i(tok, L);
             } else {
-                rem -= tot;
+                rem -= tot[u];
             }
         }
         if (result < 0) result = -wave_allreduce_i(-last_tok, MinI());   // rounding: the segment's last token with mass
@@ -424,7 +437,7 @@ __device__ __forceinline__ int locate_draw(const SampledArgs &a, int64_t j, int 
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Launch 4, second role: the loop itself.  One wave per sequence; it waits for the draws of its k+1 rows, which
+// Launch 3, second role: the loop itself.  One wave per sequence; it waits for the draws of its k+1 rows, which
 // the first role's waves of the same launch publish.
 __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int b, int lane, BlockCounters &counters, bool &stalled,
                                                        bool &stalled_before) {
@@ -519,7 +532,7 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
     return out;
 }
 
-// Launch 4: workgroups [0, n_loc_wgs) invert the running sums (one wave per draw row) and publish each draw; the
+// Launch 3: workgroups [0, n_loc_wgs) invert the running sums (one wave per draw row) and publish each draw; the
 // workgroups after them take four sequences each, wait for their rows' draws and run the loop, then apply the
 // updates as the greedy step does (sequence_counters_and_updates).  Workgroups of a launch start in index order,
 // so a sequence wave only waits for waves that have been started.
@@ -572,7 +585,7 @@ hipError_t launch_sampled_step(const StreamSource &src, const SampledArgs &a, hi
     if (a.B == 0) return hipSuccess;
     const int K1 = a.k + 1;
     const dim3 first_grid((unsigned)(a.n_stream_wgs + (a.B + kStreamWaves - 1) / kStreamWaves)), first_block(kStreamWaves * kWaveSize);
-    const int per_block = kSegBlockWaves * kSegsPerWave;
+    const int per_block = kSegItemWaves * kSegsPerWave;
     const int64_t max_items = (int64_t)a.B * K1 * ((a.nseg + per_block - 1) / per_block);
     const dim3 seg_grid((unsigned)(max_items < kSegGrid ? max_items : kSegGrid));
     const dim3 tail_grid((unsigned)(a.n_loc_wgs + (a.B + kSegBlockWaves - 1) / kSegBlockWaves)), tail_block(kSegBlockWaves * kWaveSize);
@@ -580,13 +593,13 @@ hipError_t launch_sampled_step(const StreamSource &src, const SampledArgs &a, hi
     if (a.dtype == CSD_DTYPE_F32) {
         hipLaunchKernelGGL(sampled_stream_kernel<CSD_DTYPE_F32>, first_grid, first_block, 0, stream, src, a.V, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
+        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_F32>, seg_grid, dim3(kSegItemWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_F32>, tail_grid, tail_block, 0, stream, a);
     } else {
         hipLaunchKernelGGL(sampled_stream_kernel<CSD_DTYPE_BF16>, first_grid, first_block, 0, stream, src, a.V, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_BF16>, seg_grid, dim3(kSegBlockWaves * kWaveSize), 0, stream, a);
+        hipLaunchKernelGGL(residual_segments_kernel<CSD_DTYPE_BF16>, seg_grid, dim3(kSegItemWaves * kWaveSize), 0, stream, a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         hipLaunchKernelGGL(sampled_tail_kernel<CSD_DTYPE_BF16>, tail_grid, tail_block, 0, stream, a);
     }
