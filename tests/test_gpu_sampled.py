@@ -187,10 +187,12 @@ def test_small_temperature_agrees_with_the_greedy_entry_point():
     assert decode_ocm(ocm_g) == decode_ocm(ocm_s) and len(decode_ocm(ocm_g)) > 10
 
 
-@pytest.mark.parametrize("B,k,V", [(2200, 4, 520), (3, 31, 1500), (2, 63, 900), (300, 7, 1030)])
+@pytest.mark.parametrize("B,k,V", [(2200, 4, 520), (3, 31, 1500), (2, 63, 900), (300, 7, 1030), (2, 8, 700001), (5, 3, 300000)])
 def test_large_batches_and_long_drafts(B, k, V):
     """More than 8192 draft positions (the separate update launch), k up to the limit (one lane per row in
-    the sequence kernels), several merge batches of the in-kernel update."""
+    the sequence kernels), several merge batches of the in-kernel update; huge vocabularies under a small batch
+    (more records per row than one round of loads takes, more segments per lane than the draw waves keep in
+    registers)."""
     rng = np.random.default_rng(B + k)
     ocm = csd.new_ocm(1 << 13)
     orc = O.CSDOracle()
