@@ -100,22 +100,51 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
         }
     }
 
-    // ---- remainder of the row (one workgroup per row): one guarded chunk per lane per iteration;
-    // slots past V are filled with -inf, the ragged chunk is read element by element.
+    // ---- remainder of the row (one workgroup per row): less than a tile of whole chunks, swept as one guarded
+    // tile - same chunk for (u, lane) as in a whole tile, all loads issued before any arithmetic (taken one
+    // chunk per lane at a time, this share held its place on the compute unit for five memory latencies where
+    // its neighbours need two); slots past the whole chunks are filled with -inf.  Plain loads here: with
+    // non-temporal ones the largest benchmark shape measured 1.7 microseconds slower (105.6 against 103.9; the
+    // one-chunk-at-a-time form 105.0), the small shapes the same (11.7 against 13.1, 8.7 against 9.8 per step).
+    // Then, when V is not a multiple of E, the ragged last chunk, read element by element by the one lane
+    // that owns it.
     if (has_rem) {
-        for (int it = 0; rem0 + it * WL < nchunks; ++it) {
-            const int ch = rem0 + it * WL + lane_chunk0;
-            u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
-            if (ch < nfull) {
-                q = ((const u32x4 *)rowp)[ch];
-            } else if (ch == nfull) {
-                q = C::load_ragged(rowp, nfull * E, tail);
+        {
+            u32x4 q[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int ch = rem0 + u * WL + lane_chunk0;
+                q[u].x = q[u].y = q[u].z = q[u].w = C::kNegInfWord;
+                if (ch < nfull) q[u] = ((const u32x4 *)rowp)[ch];
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {             // chunk by chunk: few registers live beside the loads
+                float x[E];
+                C::unpack(q[u], x);
+                const float cm = chunk_max<E>(x);
+                const bool up = cm > rm;
+                best_it = up ? (kRemIter + u) : best_it;
+                best_q.x = up ? q[u].x : best_q.x;
+                best_q.y = up ? q[u].y : best_q.y;
+                best_q.z = up ? q[u].z : best_q.z;
+                best_q.w = up ? q[u].w : best_q.w;
+                rm = __builtin_fmaxf(rm, cm);
+                if (__builtin_amdgcn_ballot_w64(rm > mth) != 0) rescale();
+                const float nc = -c;
+#pragma unroll
+                for (int j = 0; j < E; ++j) s[j] += __builtin_amdgcn_exp2f(__builtin_fmaf(x[j], scale, nc));
+            }
+        }
+        if (tail) {                                   // chunk nfull: lane (nfull - rem0) mod WL of the workgroup, at u = its quotient
+            const int off = nfull - rem0 - lane_chunk0;
+            const bool mine = off >= 0 && off % WL == 0;
+            u32x4 q = {C::kNegInfWord, C::kNegInfWord, C::kNegInfWord, C::kNegInfWord};
+            if (mine) q = C::load_ragged(rowp, nfull * E, tail);
             float x[E];
             C::unpack(q, x);
             const float cm = chunk_max<E>(x);
             const bool up = cm > rm;
-            best_it = up ? (kRemIter + it) : best_it;
+            best_it = up ? (kRemIter + off / WL) : best_it;
             best_q.x = up ? q.x : best_q.x;
             best_q.y = up ? q.y : best_q.y;
             best_q.z = up ? q.z : best_q.z;
