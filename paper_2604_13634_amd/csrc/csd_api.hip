@@ -443,7 +443,7 @@ int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows
     const StreamPlan plan = make_stream_plan(rows, V, dtype);
     if (partials_bytes < (size_t)rows * plan.partials_per_row * sizeof(RowPartial)) return CSD_ENOSPACE;
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, rows, nullptr, 0, CSD_LOG2E_F32};
-    return launch_row_partials(src, dtype, V, plan, partials, nullptr, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
+    return launch_row_partials(src, dtype, V, plan, partials, (hipStream_t)stream) == hipSuccess ? CSD_OK : CSD_EHIP;
 }
 
 // Test hook, deliberately absent from csd.h: spin_limit = polls a wait inside a launch may take (0 restores the

@@ -189,7 +189,7 @@ hipError_t launch_sampled_step(const StreamSource &src, const SampledArgs &a, hi
 
 // kernel launchers (enqueue only; return hipGetLastError())
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
-                               uint32_t *batch_ticket, hipStream_t stream);
+                               hipStream_t stream);
 hipError_t launch_finish(const EpilogueArgs &a, hipStream_t stream);
 hipError_t launch_verify_step(const StreamSource &src, int dtype, int V, const StreamPlan &plan, const EpilogueArgs &a,
                               hipStream_t stream);

@@ -1,6 +1,28 @@
 // The streaming pass over one row share, and the records by which streaming workgroups hand their results to
 // waves of the same launch.  Shared by the greedy step (csd_verify.hip) and the first launch of the sampled step
-// (csd_sampled.hip); the comments at the top of csd_verify.hip describe both.
+// (csd_sampled.hip).
+//
+// Streaming pass (stream_row_share).  For every verify row (a draft position or the bonus row of Algorithm 1) the
+// step needs the target distribution's normaliser, the greedy target token t* and, later, single probabilities
+// (Eq. 3 and the p_i(.) of Algorithm 1):
+//     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
+// Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
+// pass is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
+// `nsplit` contiguous runs, one per workgroup of 4 waves (dealing the tiles round-robin to the row's workgroups
+// instead measures the same); inside a tile the waves interleave 1 KiB wave-loads.
+// Each wave keeps its own running state; there is no barrier and no cross-wave step inside the sweep.
+//
+//   Per-lane state (fp32): rm = running maximum; best_q = the 16-byte chunk at which rm last strictly
+//   increased and best_it = its iteration, i.e. the first chunk of this lane that holds rm (a lane
+//   visits chunks in ascending address order, so "first" is "lowest token id"); s[E] = sums of
+//   2^(z*log2e - c), one per element slot of a chunk, against a WAVE-UNIFORM reference exponent c.
+//   c is not the running maximum: it is only kept within kRescaleGapLog2 of it (in exponent units), which is all floating point
+//   needs (no overflow, full relative precision).  A rescale (wave reduction + multiply) happens only
+//   when some lane's maximum climbs more than that above the reference - at the first tile, then
+//   almost never - so the steady-state loop is unpack, max3, fma, v_exp_f32, add and one compare per
+//   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
+//   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
+//   2^d with |d| <= ulp(c)/2: this is why logits are limited to |z| <= 2^29 (d <= 32, sums stay in range).
 #pragma once
 #include "csd_device.h"
 

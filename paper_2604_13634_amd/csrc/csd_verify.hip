@@ -1,26 +1,6 @@
 // The verification step.
 //
-// Streaming pass (stream_row_share).  For every verify row (a draft position or the bonus row of Algorithm 1) the
-// step needs the target distribution's normaliser, the greedy target token t* and, later, single probabilities
-// (Eq. 3 and the p_i(.) of Algorithm 1):
-//     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
-// Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
-// pass is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
-// `nsplit` contiguous runs, one per workgroup of 4 waves (dealing the tiles round-robin to the row's workgroups
-// instead measures the same); inside a tile the waves interleave 1 KiB wave-loads.
-// Each wave keeps its own running state; there is no barrier and no cross-wave step inside the sweep.
-//
-//   Per-lane state (fp32): rm = running maximum; best_q = the 16-byte chunk at which rm last strictly
-//   increased and best_it = its iteration, i.e. the first chunk of this lane that holds rm (a lane
-//   visits chunks in ascending address order, so "first" is "lowest token id"); s[E] = sums of
-//   2^(z*log2e - c), one per element slot of a chunk, against a WAVE-UNIFORM reference exponent c.
-//   c is not the running maximum: it is only kept within kRescaleGapLog2 of it (in exponent units), which is all floating point
-//   needs (no overflow, full relative precision).  A rescale (wave reduction + multiply) happens only
-//   when some lane's maximum climbs more than that above the reference - at the first tile, then
-//   almost never - so the steady-state loop is unpack, max3, fma, v_exp_f32, add and one compare per
-//   tile.  The exponent error of a term is half an ulp of |z*log2e - c| < 32, i.e. below 7e-7 relative;
-//   c itself is carried exactly into the combine.  c is a float near m*log2e, so the largest term is
-//   2^d with |d| <= ulp(c)/2: this is why logits are limited to |z| <= 2^29 (d <= 32, sums stay in range).
+// Streaming pass: stream_row_share in csd_stream.h (described there), one share of one row per workgroup.
 //
 // Sequence logic (sequence_decide), one wave per sequence: combine the row partials (normaliser in double),
 // draft-token ratio and probability (Eq. 3), memory lookup then gate (Algorithm 1), accepted-prefix scan by
@@ -28,8 +8,8 @@
 //
 // Three kernels put these together:
 //   verify_step_kernel   csd_verify: both parts in one launch (see the comment above it);
-//   row_partials_kernel  the streaming pass alone, one partial per wave: csd_row_partials, and the first launch
-//                        of csd_verify_sampled;
+//   row_partials_kernel  the streaming pass alone, one partial per wave: csd_row_partials (the first launch of
+//                        csd_verify_sampled has its own kernel around the same pass, csd_sampled.hip);
 //   finish_kernel        the sequence logic alone, sixteen sequences per workgroup, on partials that sit in memory
 //                        from earlier launches (csd_verify_shards).  Each workgroup takes a ticket on the batch; the
 //                        one that draws the last ticket knows that every lookup of the step has been made and
@@ -201,17 +181,11 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
 
 template <int DT>
 __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void row_partials_kernel(StreamSource src, int V, int nsplit,
-                                                                                  RowPartial *__restrict__ partials,
-                                                                                  uint32_t *batch_ticket) {
+                                                                                  RowPartial *__restrict__ partials) {
     const int row = blockIdx.x / nsplit;
     const int split = share_of_workgroup((int)blockIdx.x - row * nsplit, row, nsplit);
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    // the later kernels' two counters (the batch ticket and, on the sampled path, the length of the list of
-    // rows to draw) start every step at zero (kernel order makes this visible to them)
-    if (batch_ticket != nullptr && blockIdx.x == 0 && threadIdx.x < 2)
-        __hip_atomic_store(&batch_ticket[threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
     const char *rowp = (row < src.rows0) ? src.base0 + (int64_t)row * src.pitch0
                                          : src.base1 + (int64_t)(row - src.rows0) * src.pitch1;
     const RowPartial out = stream_row_share<DT>(rowp, V, nsplit, split, wave, lane, src.scale);
@@ -367,15 +341,13 @@ WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
 }
 
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
-                               uint32_t *batch_ticket, hipStream_t stream) {
+                               hipStream_t stream) {
     if (plan.rows == 0) return hipSuccess;
     const dim3 grid((unsigned)(plan.rows * plan.nsplit)), block(kStreamWaves * kWaveSize);
     if (dtype == CSD_DTYPE_F32)
-        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, src, V, plan.nsplit, partials,
-                           batch_ticket);
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, src, V, plan.nsplit, partials);
     else
-        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, src, V, plan.nsplit, partials,
-                           batch_ticket);
+        hipLaunchKernelGGL(row_partials_kernel<CSD_DTYPE_BF16>, grid, block, 0, stream, src, V, plan.nsplit, partials);
     return hipGetLastError();
 }
 
