@@ -229,3 +229,53 @@ def test_prior_calibration_run_counts_without_rescuing():
     orc2, ocm2, rescued2, _, _ = run_sampled_stream(w, range(25, 40), 0.6, lam=2, capacity=1 << 12,
                                                     prior=(list(before.keys()), list(before.values())))
     assert rescued2 > 0
+
+
+def test_sampled_step_replayed_from_a_captured_graph():
+    """The sampled step's three launches allocate nothing either: captured once, replayed with new logits, draft
+    tokens and uniforms copied into the captured tensors and eager work in between; each replay matches the
+    oracle, memory included.  (The replays run under one per-call number: the announcements and records of one
+    replay must not pass for the next.)"""
+    ws = SampledWorkload(CONFIGS[1], V=9001, B=12, n_pairs=16)
+    cfg = ws.cfg
+    T = 0.8
+
+    def inputs(step):
+        zp, zq, d, ua, ud = ws.sampled_step(step)
+        ua, ud = settle_uniforms(zp, zq, d, T, ua, ud, seed=step)
+        return zp, zq, d, ua, ud
+
+    zp, zq, d, ua, ud = inputs(0)
+    dev = [to_device_logits(zp), to_device_logits(zq), torch.from_numpy(d).cuda(), torch.from_numpy(ua).cuda(),
+           torch.from_numpy(ud).cuda()]
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    bf = csd.SampledBuffers.allocate(cfg.B, cfg.k, cfg.V, csd.CSD_DTYPE_BF16)
+
+    def call():
+        return csd.csd_verify_sampled(dev[0], dev[1], dev[2], T, dev[3], dev[4], cfg.tau, 1, ocm, buffers=bf)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture, then undo its updates
+        call()
+        csd.csd_ocm_reset(ocm)
+        bf.status.zero_()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    rejected = 0
+    for step in range(6):
+        zp, zq, d, ua, ud = inputs(step)
+        for t, h in zip(dev, (to_device_logits(zp), to_device_logits(zq), torch.from_numpy(d).cuda(), torch.from_numpy(ua).cuda(),
+                              torch.from_numpy(ud).cuda())):
+            t.copy_(h)
+        g.replay()
+        torch.cuda.synchronize()
+        check_sampled_step(orc, zp, zq, d, T, ua, ud, np.float32(cfg.tau), 1, bf, "sampled graph replay %d" % step)
+        compare_table(ocm, orc, "sampled graph replay %d" % step)
+        rejected += int((bf.tstar.cpu().numpy() >= 0).sum())
+        assert len(decode_ocm(ocm)) >= 0               # eager work between replays
+    assert rejected > 0 and int(bf.status[csd.CSD_STATUS_STALLED]) == 0
