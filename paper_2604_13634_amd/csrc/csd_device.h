@@ -546,7 +546,9 @@ __device__ __forceinline__ void report_stalled_sequence(int32_t *accept_len, int
 //   (`ready_seen`) and counts itself in only once it holds.  After the barrier every workgroup has seen it, and the
 //   first sequence workgroup clears it, so that a replay of the same launch (same number) waits for its own
 //   set-up; a workgroup whose wait ran out clears it as well.  Nothing here needs an answer after the barrier:
-//   the increments and the clearing store travel while the kernel ends.
+//   the increments and the clearing store travel while the kernel ends.  A launch with a single sequence
+//   workgroup (up to four sequences) skips all of it: the workgroup barrier at the top already orders its
+//   lookups before its updates (1.5 microseconds of a 9 microsecond step).
 __device__ __forceinline__ uint64_t step_ready_value(uint64_t nonce) { return mix64(nonce ^ 0x5244595f43534431ull) | 1ull; }
 
 __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t ready_seen, uint64_t ready_value,
@@ -559,7 +561,8 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
         atomicAdd(&status[threadIdx.x], counters.v[threadIdx.x]);
     if (!update_here) return;
     bool good = true;
-    if (threadIdx.x == 0) {
+    const bool alone = total <= 1;                   // one sequence workgroup: its own barrier above was the barrier
+    if (threadIdx.x == 0 && !alone) {
         for (uint32_t spin = 0; ready_seen != ready_value; ++spin) {
             if (spin >= spin_limit) { good = false; break; }
             __builtin_amdgcn_s_sleep(kSpinSleep);
@@ -570,7 +573,7 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
     OcmClaim claim = {CSD_OCM_EMPTY, false, false};
     if (dv.counted) claim = ocm_claim_after_probe(ocm, dv.key, dv.probe);
     if (threadIdx.x == 0) {
-        if (good) {
+        if (good && !alone) {
             for (uint32_t spin = 0;; ++spin) {
                 if (__hip_atomic_load(&ctrl->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= total) break;
                 if (spin >= spin_limit) { good = false; break; }
@@ -580,7 +583,7 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
         if (!good) {
             xwg_store64(&ctrl->ready, 0ull);
             if (status != nullptr) atomicAdd(&status[CSD_STATUS_STALLED], 1u);
-        } else if (first_sequence_workgroup) {
+        } else if (first_sequence_workgroup && !alone) {
             xwg_store64(&ctrl->ready, 0ull);
         }
         *verdict = good ? 1 : 0;
