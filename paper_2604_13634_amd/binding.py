@@ -165,14 +165,8 @@ def _current_stream_handle() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
-               ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
-               buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True,
-               static_scratch: bool = False) -> VerifyBuffers:
-    """Enqueue one verification step.  logits: [B][k+1][V] (float32 or bfloat16), draft: [B][k] int32.
-
-    Returns the VerifyBuffers holding the outputs (valid once the stream has run the call).
-    With diagnostics=False the optional outputs (row_max ... rej_log) are not written."""
+def _marshal_verify(logits, draft, tau, lam, ocm, flags, buffers, stream, diagnostics, static_scratch):
+    """Checks and argument list of one csd_verify / csd_verify_static call: (C function, its arguments, buffers, name)."""
     if logits.dim() != 3:
         raise ValueError("logits must be [B][k+1][V]")
     B, K1, V = logits.shape
@@ -205,19 +199,52 @@ def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, 
         st = _current_stream_handle()
     else:
         st = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    head = (logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
+            None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags)
     if static_scratch:
-        rc = load_library().csd_verify_static(
-            logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
-            None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags, *outs[:10], st or None)
-        if rc != CSD_OK:
-            raise CsdError(rc, "csd_verify_static")
-        return bf
-    rc = load_library().csd_verify(
-        logits.data_ptr(), dt, row_stride, None if draft is None else draft.data_ptr(), B, k, V, tau, lam & 0xFFFFFFFF,
-        None if ocm is None else ocm.data_ptr(), 0 if ocm is None else ocm.numel(), flags, *outs, st or None)
+        return load_library().csd_verify_static, head + outs[:10] + (st or None,), bf, "csd_verify_static"
+    return load_library().csd_verify, head + outs + (st or None,), bf, "csd_verify"
+
+
+def csd_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
+               ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+               buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True,
+               static_scratch: bool = False) -> VerifyBuffers:
+    """Enqueue one verification step.  logits: [B][k+1][V] (float32 or bfloat16), draft: [B][k] int32.
+
+    Returns the VerifyBuffers holding the outputs (valid once the stream has run the call).
+    With diagnostics=False the optional outputs (row_max ... rej_log) are not written."""
+    fn, args, bf, name = _marshal_verify(logits, draft, tau, lam, ocm, flags, buffers, stream, diagnostics, static_scratch)
+    rc = fn(*args)
     if rc != CSD_OK:
-        raise CsdError(rc, "csd_verify")
+        raise CsdError(rc, name)
     return bf
+
+
+class PreparedVerify:
+    """One csd_verify call with its arguments checked and marshalled once, for loops that verify into the same
+    tensors step after step (a serving loop refills `logits` and `draft` in place): `launch()` is the C call and
+    nothing else.  The tensors, the buffers and the stream handed to `prepare_verify` must stay alive and in
+    place; `stream=None` fixes the stream that was current when the call was prepared."""
+    __slots__ = ("_fn", "_args", "_name", "buffers", "_keep")
+
+    def __init__(self, fn, args, name, buffers, keep):
+        self._fn, self._args, self._name, self.buffers, self._keep = fn, args, name, buffers, keep
+
+    def launch(self) -> VerifyBuffers:
+        rc = self._fn(*self._args)
+        if rc != CSD_OK:
+            raise CsdError(rc, self._name)
+        return self.buffers
+
+
+def prepare_verify(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,
+                   ocm: Optional[torch.Tensor] = None, flags: int = CSD_APPLY_UPDATES,
+                   buffers: Optional[VerifyBuffers] = None, stream=None, diagnostics: bool = True,
+                   static_scratch: bool = False) -> PreparedVerify:
+    """The arguments of csd_verify, checked and marshalled once; see PreparedVerify."""
+    fn, args, bf, name = _marshal_verify(logits, draft, tau, lam, ocm, flags, buffers, stream, diagnostics, static_scratch)
+    return PreparedVerify(fn, args, name, bf, (logits, draft, ocm, stream))
 
 
 def csd_verify_static(logits: torch.Tensor, draft: Optional[torch.Tensor], tau: float, lam: int,

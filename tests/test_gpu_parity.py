@@ -789,6 +789,30 @@ def test_step_replayed_from_a_captured_graph():
         assert int(csd.csd_ocm_lookup(ocm, torch.tensor([(1 << 20) | 2], dtype=torch.int64, device="cuda"))[0]) >= 0   # eager work between replays
 
 
+def test_prepared_calls_run_the_same_step():
+    """prepare_verify checks and marshals the arguments once; launch() then only makes the C call.  A stream run
+    through one prepared call, its logits and draft tokens refilled in place, matches the oracle step by step -
+    on the caller's workspace and on the library's static scratch."""
+    w = Workload(CONFIGS[1], V=9001, B=6)
+    cfg = w.cfg
+    z0, d0 = w.step(0)
+    zt, dt = to_device_logits(z0), torch.from_numpy(d0).cuda()
+    for static in (False, True):
+        ocm = csd.new_ocm(1 << 12)
+        orc = O.CSDOracle()
+        call = csd.prepare_verify(zt, dt, cfg.tau, cfg.lam, ocm, static_scratch=static)
+        for step in range(8):
+            z, d = w.step(step)
+            zt.copy_(to_device_logits(z))
+            dt.copy_(torch.from_numpy(d).cuda())
+            bf = call.launch()
+            torch.cuda.synchronize()
+            compare_step(orc.verify_step(z, d, tau=np.float32(cfg.tau), lam=cfg.lam), bf, "prepared step %d" % step)
+        compare_table(ocm, orc, "prepared, static=%s" % static)
+    with pytest.raises(ValueError):
+        csd.prepare_verify(zt, dt[:, :-1].contiguous(), cfg.tau, cfg.lam, ocm)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_largest_vocabulary_and_smallest_table(dtype):
     """V = 2^20 (the largest the packed pair allows), with the top token at the very end and a tie across
