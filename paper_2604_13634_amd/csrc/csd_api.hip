@@ -372,14 +372,14 @@ int csd_verify_sampled(const void *target_logits, const void *draft_logits, int 
     a.n_loc_wgs = sampled_locate_workgroups(B, k);
     // as in csd_verify: few sequence workgroups wait for each other and apply the updates themselves, many hand the
     // log to the bulk update kernel
-    const bool update_in_finish = apply && sampled_sequence_workgroups(B) <= kMaxBarrierWorkgroups;
-    a.update_here = update_in_finish ? 1 : 0;
-    if (update_in_finish && !rej_log) a.rej_log = nullptr;   // nobody reads a log then
+    const bool update_in_tail = apply && sampled_sequence_workgroups(B) <= kMaxBarrierWorkgroups;
+    a.update_here = update_in_tail ? 1 : 0;
+    if (update_in_tail && !rej_log) a.rej_log = nullptr;   // nobody reads a log then
 
     const StreamSource src = {(const char *)target_logits, target_row_stride * (int64_t)esz, rows_p,
                               (const char *)draft_logits, draft_row_stride * (int64_t)esz, scale};
     if (launch_sampled_step(src, a, st) != hipSuccess) return CSD_EHIP;
-    if (apply && !update_in_finish) {
+    if (apply && !update_in_tail) {
         if (launch_ocm_update(ocm, capacity, a.rej_log, nullptr, (uint64_t)B * (uint64_t)k, nullptr, status, st) != hipSuccess)
             return CSD_EHIP;
     }

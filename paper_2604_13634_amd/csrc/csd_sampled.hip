@@ -250,8 +250,9 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void sampled_stream_ker
 // ---------------------------------------------------------------------------------------------------
 // Launch 2: residual mass per segment, for the rows on the list only.  One workgroup per item (row of the list,
 // group of segments); the grid is sized for every row needing a draw (up to kSegGrid workgroups, which then take
-// several items each) and the workgroups beyond the list's end leave at once.  (A fixed grid of 4096 workgroups walking the items measured 1.5 % slower on the whole step,
-// workgroups of 1, 2 and 8 waves 1 - 2.5 % slower than these 4.)
+// several items each) and the workgroups beyond the list's end leave at once.  (A fixed grid of 4096 workgroups
+// walking the items measured 1.5 % slower on the whole step, workgroups of 1, 2 and 8 waves 1 - 2.5 % slower than
+// these 4.)
 template <int DT>
 __global__ __launch_bounds__(kSegItemWaves *kWaveSize) void residual_segments_kernel(SampledArgs a) {
     using C = Chunk<DT>;

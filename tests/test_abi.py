@@ -51,6 +51,25 @@ def test_workspace_query_is_pure_host_arithmetic():
         assert b.csd_verify_workspace_bytes(*bad) == 0
 
 
+def test_launch_plan_of_the_streaming_pass():
+    """How many workgroups share a row (host arithmetic, visible through csd_row_partials_per_row = 4 waves per
+    workgroup): two 32 KiB tiles per workgroup in general; every tile, and the row's remainder, a workgroup of its
+    own when the whole launch is at most 1024 workgroups; three tiles where two would leave it just above that."""
+    from paper_2604_13634_amd import binding as csd
+    per_row = lambda rows, V, dt: csd.csd_row_partials_per_row(rows, V, dt) // 4
+    F32, BF16 = csd.CSD_DTYPE_F32, csd.CSD_DTYPE_BF16
+    assert per_row(256 * 5, 256000, BF16) == 8       # 15 tiles and a remainder: 7 x 2 tiles, 1 tile + remainder
+    assert per_row(64 * 9, 152064, F32) == 9         # 18 tiles and a remainder
+    assert per_row(32 * 8, 151936, BF16) == 3        # 9 tiles: 256 x 5 workgroups would be 1280 > 1024, 256 x 3 fit
+    assert per_row(8 * 6, 128256, BF16) == 8         # small launch: 7 tiles + the remainder, one round of loads each
+    assert per_row(1 * 5, 32000, F32) == 4           # 3 tiles + the remainder
+    assert per_row(5, 8 * 2048 * 3, BF16) == 3       # exactly three tiles, no remainder
+    assert per_row(7, 100, F32) == 1                 # less than a tile
+    for B, k, V, dt in [(256, 4, 256000, BF16), (64, 8, 152064, F32), (1, 4, 32000, F32), (3, 0, 7, BF16)]:
+        rows = B * (k + 1)                            # control head, one 32-byte record per streaming workgroup, the log
+        assert csd.csd_verify_workspace_bytes(B, k, V, dt) >= 256 + rows * per_row(rows, V, dt) * 32 + B * k * 8
+
+
 def test_argument_errors_are_synchronous_and_enqueue_nothing():
     """Every call below fails validation on the host, so no pointer is ever dereferenced."""
     from paper_2604_13634_amd import binding as b
