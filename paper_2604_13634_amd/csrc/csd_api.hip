@@ -143,6 +143,9 @@ static int verify_step(const void *logits, int dtype, int64_t row_stride, const 
     a.reader_nonce = a.nonce ^ g_reader_nonce_xor.load(std::memory_order_relaxed);
     a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
     a.n_stream_wgs = plan.rows * plan.nsplit;
+    a.n_seq_wgs = n_seq_wgs;
+    a.order = make_step_order(plan, B, k);
+    a.seq_words = (WordRecord *)((char *)workspace + ws.words_off);
     const StreamSource src = {(const char *)logits, row_stride * (int64_t)esz, plan.rows, nullptr, 0, CSD_LOG2E_F32};
     if (launch_verify_step(src, dtype, V, plan, a, st) != hipSuccess) return CSD_EHIP;
     if (apply && !update_here) {
@@ -451,6 +454,15 @@ int csd_row_partials(const void *logits, int dtype, int64_t row_stride, int rows
 void csd_test_set_wait_rules(uint32_t spin_limit, uint64_t reader_nonce_xor) {
     g_spin_limit.store(spin_limit ? spin_limit : (1u << 21), std::memory_order_relaxed);
     g_reader_nonce_xor.store(reader_nonce_xor, std::memory_order_relaxed);
+}
+
+// Test hook, deliberately absent from csd.h: the grid order of csd_verify's launch - 0 chosen by shape (the default),
+// 1 always the plain order, 2 the bonus rows last whenever there is a draft position.  Affects calls enqueued afterwards.
+void csd_test_set_step_order(int order) { set_step_order_override(order); }
+// 1 when csd_verify streams the bonus rows of this shape last, 0 for the plain order, -1 for a bad shape (host arithmetic)
+int csd_test_step_order_of(int B, int k, int V, int dtype) {
+    if (!shape_ok(B, k, V, dtype)) return -1;
+    return make_step_order(make_stream_plan(B * (k + 1), V, dtype), B, k).bonus_last;
 }
 
 const char *csd_strerror(int code) {

@@ -137,7 +137,7 @@ __device__ inline OcmProbe ocm_probe(const uint64_t *ocm, uint64_t capacity, uin
 // First half of an insert, usable before the step's other lookups have finished: claim the empty slot the probe
 // ended at for `key`, with count ZERO.  A pair that is absent and a pair that is present with count zero read
 // the same in every lookup, so this changes no decision of the step; the count is added later.  The result
-// (`won`, and what the slot held otherwise) is first looked at in ocm_add_one_after_claim, so the
+// (`won`, and what the slot held otherwise) is first looked at in ocm_add_after_claim, so the
 // compare-and-swap can stay in flight while the caller does other things.
 struct OcmClaim {
     uint64_t seen;       // content of the slot when the claim lost
@@ -157,16 +157,17 @@ __device__ __forceinline__ OcmClaim ocm_claim_after_probe(uint64_t *ocm, uint64_
 constexpr uint32_t kHintHeadroom = 1u << 20;   // increments by others allowed for between a probe and the add that uses it
 
 // Second half: the pair sits at pr.slot (found by the probe, or claimed there since - by this lane or, a moment
-// ago, by another lane of the step) and takes one atomic add; anything else goes the general way.
-__device__ inline bool ocm_add_one_after_claim(uint64_t *ocm, uint64_t capacity, uint64_t key, const OcmProbe &pr,
-                                               const OcmClaim &c) {
+// ago, by another lane of the step) and takes one atomic add of w (a workgroup's occurrences of the pair, far below
+// the headroom); anything else goes the general way.
+__device__ inline bool ocm_add_after_claim(uint64_t *ocm, uint64_t capacity, uint64_t key, uint32_t w, const OcmProbe &pr,
+                                           const OcmClaim &c) {
     const bool here = (pr.found && pr.count < CSD_OCM_COUNT_MAX - kHintHeadroom) ||
                       (c.tried && (c.won || (slot_key(c.seen) == key && slot_count(c.seen) < CSD_OCM_COUNT_MAX - kHintHeadroom)));
     if (here) {
-        __hip_atomic_fetch_add(&ocm[pr.slot], 1ull << CSD_OCM_KEY_BITS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&ocm[pr.slot], (uint64_t)w << CSD_OCM_KEY_BITS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }
-    return ocm_add(ocm, capacity, key, 1u);
+    return ocm_add(ocm, capacity, key, w);
 }
 
 // A workgroup barrier that waits for LDS traffic only: values handed round through LDS are complete, stores and
@@ -509,11 +510,42 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
     return x;
 }
 
+// Divergences of one sequence workgroup that name the same pair reach the table as ONE add of their number.
+// Atomic adds that meet on one address are applied one after the other where the eight XCDs agree, about 12 ns
+// each (1024 adds to one word from 64 workgroups: 12.5 microseconds until the last is acknowledged; to distinct
+// words: 0.7), so a step whose sequences all diverge on one pair would spend longer on its updates than on its
+// logits.  A small LDS hash table, cleared when the workgroup starts, slots laid out as in the memory itself
+// (count above the pair): the lane that puts a pair in is the pair's leader and adds the slot's count to the memory
+// once the workgroup's barrier has passed.  Sized to hold every position of a sequence workgroup (4 waves of at
+// most 63 positions); kept at 2 KiB because a workgroup of the streaming kernel that statically holds 6 KiB of LDS
+// measured 0.8 microseconds slower per step on the fp32 shape (3 KiB: no difference).
+constexpr int kMergeSlots = 256;
+struct StepMergeLds {
+    unsigned long long slot[kMergeSlots];
+};
+__device__ __forceinline__ void step_merge_clear(StepMergeLds &M) {   // every thread; a workgroup barrier must follow
+    for (int i = threadIdx.x; i < kMergeSlots; i += blockDim.x) M.slot[i] = CSD_OCM_EMPTY;
+}
+// returns the pair's slot; `leader` is true in the one lane of the workgroup that put the pair there
+__device__ __forceinline__ int step_merge_insert(StepMergeLds &M, uint64_t key, bool &leader) {
+    uint32_t i = (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> 40) & (kMergeSlots - 1);
+    for (;;) {
+        const unsigned long long cur = atomicCAS(&M.slot[i], (unsigned long long)CSD_OCM_EMPTY, (unsigned long long)key);
+        leader = (cur == CSD_OCM_EMPTY);
+        if (leader || slot_key(cur) == key) {
+            atomicAdd(&M.slot[i], 1ull << CSD_OCM_KEY_BITS);
+            return (int)i;
+        }
+        i = (i + 1) & (kMergeSlots - 1);
+    }
+}
+
 // What a lane carries out of the verification loop for the update phase.
 struct Divergence {
     bool counted;        // this position's pair goes to UpdateMemory
     uint64_t key;
     OcmProbe probe;      // where the lookup ended (only when probed)
+    int n;               // the sequence's accepted length (wave-uniform)
 };
 
 
@@ -554,8 +586,8 @@ __device__ __forceinline__ uint64_t step_ready_value(uint64_t nonce) { return mi
 __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl, uint64_t ready_seen, uint64_t ready_value,
                                                               bool first_sequence_workgroup, uint32_t total, bool update_here,
                                                               uint64_t *ocm, uint64_t capacity, uint32_t *status,
-                                                              BlockCounters &counters, const Divergence &dv, int *verdict,
-                                                              uint32_t spin_limit) {
+                                                              BlockCounters &counters, StepMergeLds &merge,
+                                                              const Divergence &dv, int *verdict, uint32_t spin_limit) {
     barrier_lds_only();
     if (status != nullptr && threadIdx.x < CSD_STATUS_WORDS && counters.v[threadIdx.x] != 0)
         atomicAdd(&status[threadIdx.x], counters.v[threadIdx.x]);
@@ -572,6 +604,10 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
     }
     OcmClaim claim = {CSD_OCM_EMPTY, false, false};
     if (dv.counted) claim = ocm_claim_after_probe(ocm, dv.key, dv.probe);
+    // while the barrier is pending: equal pairs of this workgroup find each other (step_merge_insert)
+    bool leader = false;                             // this lane sends its pair's increments for the whole workgroup
+    int mslot = 0;
+    if (dv.counted) mslot = step_merge_insert(merge, dv.key, leader);
     if (threadIdx.x == 0) {
         if (good && !alone) {
             for (uint32_t spin = 0;; ++spin) {
@@ -589,9 +625,10 @@ __device__ __forceinline__ void sequence_counters_and_updates(StepControl *ctrl,
         *verdict = good ? 1 : 0;
     }
     barrier_lds_only();
-    if (*verdict != 0 && dv.counted) {
-        if (!ocm_add_one_after_claim(ocm, capacity, dv.key, dv.probe, claim) && status != nullptr)
-            atomicAdd(&status[CSD_STATUS_DROPPED], 1u);
+    if (*verdict != 0 && leader) {
+        const uint32_t weight = slot_count(merge.slot[mslot]);
+        if (!ocm_add_after_claim(ocm, capacity, dv.key, weight, dv.probe, claim) && status != nullptr)
+            atomicAdd(&status[CSD_STATUS_DROPPED], weight);
     }
 }
 

@@ -59,15 +59,28 @@ struct StepControl {
     uint32_t pad;
 };
 
-// csd_verify workspace: [control | records | rejection log].  Nothing but the control head outlives a call.
+// csd_verify workspace: [control | records | rejection log | sequence words].  Nothing in it outlives a call.
 struct WorkspaceLayout {
     size_t ticket_off;                       // the control head (the ticket of the two-launch forms lives here too)
     size_t partials_off, partials_bytes;     // StepRecord per streaming workgroup
     size_t log_off, log_bytes;
+    size_t words_off, words_bytes;           // WordRecord per sequence (bonus-rows-last order only)
     size_t total;
 };
 
 WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k);
+
+// Grid order of the single-launch step.  Plain order: every row's streaming workgroups in row order, then the
+// sequence workgroups.  Bonus-rows-last order (launches too large to be resident at once): the streaming workgroups
+// of the draft positions' rows, those of the bonus rows, the sequence workgroups (which take the draft positions'
+// rows only), and one more set of workgroups that takes the bonus rows' statistics.  A pure function of the shape.
+struct StepOrder {
+    int bonus_last;        // 0: plain order
+    int n_draft_wgs;       // streaming workgroups of the draft positions' rows (B * k * nsplit)
+};
+StepOrder make_step_order(const StreamPlan &p, int B, int k);
+void set_step_order_override(int v);                 // test hook: 0 by shape, 1 always plain, 2 bonus rows last whenever k >= 1
+constexpr int kResidentWorkgroups = 4 * 256;         // streaming workgroups resident at once (four per compute unit)
 
 // Everything the per-sequence epilogue and the update phase need.
 struct EpilogueArgs {
@@ -105,8 +118,11 @@ struct EpilogueArgs {
     uint64_t nonce;          // per-call number behind the records' check words
     uint64_t reader_nonce;   // the same number as the readers use it (a test hook can make them differ: nothing then passes)
     uint32_t spin_limit;     // polls after which a wait inside the launch gives up
-    int n_stream_wgs;        // workgroups [0, n_stream_wgs) stream rows, the rest take sequences
+    int n_stream_wgs;        // streaming workgroups of the launch (plain order: workgroups [0, n_stream_wgs); the rest take sequences)
     int update_here;         // 1: the sequence waves apply their own increments after a barrier among their workgroups
+    int n_seq_wgs;           // sequence workgroups
+    StepOrder order;         // where they sit in the grid
+    WordRecord *seq_words;   // [B] bonus-rows-last order: what a sequence's loop hands to the wave that takes its bonus row
 };
 
 // Where the rows of a streaming launch live: rows [0, rows0) in tensor 0, the others in tensor 1

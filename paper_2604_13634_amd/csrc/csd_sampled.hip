@@ -540,6 +540,7 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
 template <int DT>
 __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel(SampledArgs a) {
     __shared__ BlockCounters counters;
+    __shared__ StepMergeLds merge;
     __shared__ int verdict;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
@@ -557,6 +558,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
     const int b = wg * kSegBlockWaves + wave;
     uint64_t ready_seen = 0;
     if (a.update_here && threadIdx.x == 0) ready_seen = xwg_load64(&a.ctrl->ready);
+    if (a.update_here) step_merge_clear(merge);
     block_counters_clear(counters);
     Divergence dv;
     dv.counted = false;
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
         }
     }
     sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)n_seq_wgs,
-                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, dv, &verdict, a.spin_limit);
+                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, merge, dv, &verdict, a.spin_limit);
 }
 
 }  // namespace

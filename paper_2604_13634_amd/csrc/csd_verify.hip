@@ -20,6 +20,8 @@
 //                        are acknowledged before the workgroup barrier that precedes the ticket, itself an
 //                        agent-scope atomic add.  (A release/acquire fence pair would do the same job by writing
 //                        back and invalidating a whole L2 per wave, which measured ten times the streaming pass.)
+#include <atomic>
+
 #include "csd_stream.h"
 
 namespace csd {
@@ -55,13 +57,13 @@ __device__ __forceinline__ int lanes_per_row(int K1) {
     return G;
 }
 
-// Row statistics held by the first lane of each row's group -> outputs, and to the position layout
-// (lane i gets the statistics of row i; lanes >= K1 read row 0, unused).
-__device__ __forceinline__ void publish_row_stats(const EpilogueArgs &a, int b, int lane, int G, float gm, int t, double S,
-                                                  float &rmax, int &tstar, double &rS) {
+// Row statistics held by the first lane of each row's group (rows 0 .. nrows-1 of the sequence) -> outputs, and to
+// the position layout (lane i gets the statistics of row i; lanes >= K1 read row 0, unused).
+__device__ __forceinline__ void publish_row_stats(const EpilogueArgs &a, int b, int lane, int G, int nrows, float gm, int t,
+                                                  double S, float &rmax, int &tstar, double &rS) {
     const int K1 = a.k + 1;
     const int grow = lane / G, gs = lane & (G - 1);
-    if (grow < K1 && gs == 0) {
+    if (grow < nrows && gs == 0) {
         const int64_t row = (int64_t)b * K1 + grow;
         a.argmax[row] = t;
         if (a.row_max) a.row_max[row] = gm;
@@ -76,9 +78,11 @@ __device__ __forceinline__ void publish_row_stats(const EpilogueArgs &a, int b, 
 // Algorithm 1 for one sequence, given its row statistics: ratio (Eq. 3), match, memory lookup, gate, accepted
 // prefix, emitted token, outputs and the per-workgroup status counters.  PROBE: keep where each lookup ended
 // (for updates applied straight from these lanes); the lookup is then made even when lambda == 0.
+// bonus_known: lane k holds the bonus row's t*; without it the emitted token of a sequence that keeps all its
+// draft tokens is left to whoever takes the bonus row (the loop itself never reads that row).
 template <bool PROBE>
 __device__ __forceinline__ Divergence sequence_decide(const EpilogueArgs &a, int b, int lane, const DraftLane &dl, float rmax,
-                                                      int tstar, double rS, BlockCounters &counters) {
+                                                      int tstar, double rS, bool bonus_known, BlockCounters &counters) {
     const int k = a.k;
     const bool is_pos = lane < k;
     const int d = dl.d;
@@ -118,6 +122,7 @@ __device__ __forceinline__ Divergence sequence_decide(const EpilogueArgs &a, int
     const bool counted = processed && diverges;
     const int next = from_lane_i(tstar, n);                    // row n: stopping position or bonus row
     out.counted = counted;
+    out.n = n;
 
     if (is_pos) {
         const int64_t o = (int64_t)b * k + lane;
@@ -138,7 +143,7 @@ __device__ __forceinline__ Divergence sequence_decide(const EpilogueArgs &a, int
     const uint64_t m_bad = __builtin_amdgcn_ballot_w64(processed && !valid);
     if (lane == 0) {
         a.accept_len[b] = n;
-        a.next_token[b] = next;
+        if (bonus_known || n < k) a.next_token[b] = next;
         if (m_bad) atomicAdd(&counters.v[CSD_STATUS_BAD_DRAFT], (unsigned int)__builtin_popcountll(m_bad));
         if (m_rescued) atomicAdd(&counters.v[CSD_STATUS_RESCUED], (unsigned int)__builtin_popcountll(m_rescued));
         if (m_counted) atomicAdd(&counters.v[CSD_STATUS_COUNTED], (unsigned int)__builtin_popcountll(m_counted));
@@ -175,8 +180,8 @@ __device__ __forceinline__ void sequence_epilogue(const EpilogueArgs &a, int b, 
     float rmax;
     int tstar;
     double rS;
-    publish_row_stats(a, b, lane, G, gm, t, S, rmax, tstar, rS);
-    sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, counters);
+    publish_row_stats(a, b, lane, G, K1, gm, t, S, rmax, tstar, rS);
+    sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, true, counters);
 }
 
 template <int DT>
@@ -218,45 +223,62 @@ __global__ __launch_bounds__(kApplyThreads) void finish_kernel(EpilogueArgs a) {
 //
 // Memory updates: with at most kMaxBarrierWorkgroups sequence workgroups (all resident together, so they can
 // wait for each other) each workgroup counts itself in on the control head once its lookups are done, waits
-// until all have, and then every lane adds its own pair straight to the table at the slot its lookup ended at
-// (the slot of an absent pair is claimed with count zero while the workgroup waits): all lookups of the step
-// precede all its updates, and no log is re-read.  The first workgroup of the launch zeroes that counter and
-// then says so in the control head; the sequence workgroups count themselves in only after seeing that, and
-// clear the word after the barrier (so nothing in the workspace has to survive from one call to the next).
+// until all have, and then adds its pairs straight to the table at the slots its lookups ended at - one add per
+// distinct pair of the workgroup, carrying the number of its lanes that hold the pair (the slot of an absent pair
+// is claimed with count zero while the workgroup waits): all lookups of the step precede all its updates, and no
+// log is re-read.  The first workgroup of the launch zeroes that counter and then says so in the control head; the
+// sequence workgroups count themselves in only after seeing that, and clear the word after the barrier (so nothing
+// in the workspace has to survive from one call to the next).
+//
+// Two grid orders (make_step_order).  Plain: rows in row order, then the sequence workgroups, which take all k+1
+// rows of their sequences in one round of record loads.  Bonus rows last (launches too large to be resident at
+// once): the rows of the draft positions, then the bonus rows, then the sequence workgroups, which take the draft
+// positions' rows only - all the loop, the lookups, the barrier and the updates depend on - and so start before the
+// stream has ended; a last set of workgroups takes the bonus rows' statistics and the emitted token of sequences
+// that kept every draft token (step_bonus_rows), one round trip after the last streaming workgroup.
 //
 // Measured against the two-launch form (streaming kernel, then a kernel of sequence waves) on the five
 // benchmark shapes: 15.0 -> 10.3, 17.8 -> 13.2, 29.3 -> 23.8, 68.2 -> 59.8 and 106.7 -> 104.5 microseconds per
-// step.  Memory round trips cost about 1 us on an idle chip and about 3 us while the rows are being streamed,
+// step.  Memory round trips cost about 1 us on an idle chip and 3 - 5 us while the rows are being streamed,
 // which is why the sequence waves sit at the END of the grid (they start when the last streaming workgroups do,
-// and do their dependent loads when the chip falls quiet).  Tried and dropped: streaming the bonus rows last and
-// running loop, barrier and updates under them (the dependent chain then runs at loaded latency, and waves
-// resident early take places from the streaming workgroups: 1-5 us slower on four of the five shapes); waiting
-// on one record per sequence before polling all (no gain once records are one per workgroup); per-wave records
-// (three rounds of loads at k = 8).
+// and do their dependent loads when the chip falls quiet).  Tried and dropped: sequence workgroups placed earlier
+// in the grid (see make_step_order); waiting on one record per sequence before polling all (no gain once records
+// are one per workgroup); per-wave records (three rounds of loads at k = 8).
 
 
-__device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCounters &counters, int *verdict) {
+// What a sequence's loop leaves for the wave that takes its bonus row (bonus-rows-last order): the accepted length,
+// or this mark when the loop's own wait ran out.
+constexpr uint64_t kSeqWordStalled = 0xFFFFFFFFull;
+
+// A sequence workgroup: four sequences, one wave each.  wg = its number among the n_seq_wgs sequence workgroups.
+// Plain order: the statistics of all k+1 rows, the loop, the emitted token.  Bonus-rows-last order: the rows of
+// the draft positions only - everything the lookups, the barrier and the updates depend on - while the bonus rows
+// are still being streamed; the accepted length is handed on in a published word.
+__device__ __forceinline__ void step_sequences(const EpilogueArgs &a, int wg, BlockCounters &counters, StepMergeLds &merge,
+                                               int *verdict) {
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wg = (int)blockIdx.x - a.n_stream_wgs;
-    const int n_seq_wgs = (int)gridDim.x - a.n_stream_wgs;
     const int b = wg * kStepSeqWaves + (threadIdx.x >> 6);
     const int k = a.k, K1 = a.k + 1;
+    const bool bonus_later = a.order.bonus_last != 0;
+    const int nrows = bonus_later ? k : K1;          // rows whose statistics this wave takes
     // thread 0 will need the control head set up: ask early, look at the answer late
     uint64_t ready_seen = 0;
     if (a.update_here && threadIdx.x == 0) ready_seen = xwg_load64(&a.ctrl->ready);
+    if (a.update_here) step_merge_clear(merge);
     block_counters_clear(counters);
 
     Divergence dv;
     dv.counted = false;
     dv.key = 0;
     dv.probe = OcmProbe{0, 0, false, false};
+    dv.n = 0;
     bool stalled = false;
     if (b < a.B) {                                   // wave-uniform: a wave takes a sequence or none
         const DraftLane dl = load_draft_lane<false>(a, b, lane);
         const int P = a.shard_per_row[0];
         const int G = lanes_per_row(K1);
         const int grow = lane / G, gs = lane & (G - 1);
-        const bool active = grow < K1;
+        const bool active = grow < nrows;
         const int64_t prow = (int64_t)b * K1 + (active ? grow : 0);
         StepRecord *row_rec = a.records + prow * P;
         const uint64_t rec0 = (uint64_t)prow * (uint64_t)P;
@@ -269,17 +291,61 @@ __device__ __forceinline__ void step_sequences(const EpilogueArgs &a, BlockCount
             float rmax;
             int tstar;
             double rS;
-            publish_row_stats(a, b, lane, G, gm, t, S, rmax, tstar, rS);
-            if (a.update_here) dv = sequence_decide<true>(a, b, lane, dl, rmax, tstar, rS, counters);
-            else dv = sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, counters);
+            publish_row_stats(a, b, lane, G, nrows, gm, t, S, rmax, tstar, rS);
+            if (a.update_here) dv = sequence_decide<true>(a, b, lane, dl, rmax, tstar, rS, !bonus_later, counters);
+            else dv = sequence_decide<false>(a, b, lane, dl, rmax, tstar, rS, !bonus_later, counters);
         } else {                                     // the records never came: say so, and report nothing as accepted
             report_stalled_sequence(a.accept_len, a.next_token, a.pos_flags, a.rej_log, b, k, lane);
             if (lane == 0) atomicAdd(&counters.v[CSD_STATUS_STALLED], 1u);
         }
+        if (bonus_later && lane == 0)
+            publish_word(a.seq_words + b, a.nonce, (uint64_t)b, stalled ? kSeqWordStalled : (uint64_t)(uint32_t)dv.n);
     }
 
-    sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)n_seq_wgs,
-                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, dv, verdict, a.spin_limit);
+    sequence_counters_and_updates(a.ctrl, ready_seen, step_ready_value(a.reader_nonce), wg == 0, (uint32_t)a.n_seq_wgs,
+                                  a.update_here != 0, a.ocm, a.capacity, a.status, counters, merge, dv, verdict, a.spin_limit);
+}
+
+// Bonus-rows-last order, the workgroups at the very end of the grid: one wave per sequence takes the statistics of
+// the sequence's bonus row (nothing but these outputs depends on that row) and, when the loop kept every draft
+// token, the emitted token.  It waits for the bonus row's records and for the word its sequence's loop left -
+// both published by workgroups earlier in the grid.  A loop that reported a stall has reported everything; a
+// bonus row whose records never come is counted as a stall of its own and the emitted token, if it was to come
+// from that row, reads -1.
+__device__ __forceinline__ void step_bonus_rows(const EpilogueArgs &a, int wg) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int b = wg * kStepSeqWaves + (threadIdx.x >> 6);
+    if (b >= a.B) return;                            // wave-uniform
+    const int k = a.k, K1 = a.k + 1, P = a.shard_per_row[0];
+    const int64_t row = (int64_t)b * K1 + k;
+    // the word first: it has been there for a while, and its loads travel with the records' first round
+    WordRecord *word = a.seq_words + b;
+    uint64_t wv = 0, wc = 0;
+    if (lane == 0) {
+        wv = xwg_load64(&word->value);
+        wc = xwg_load64(&word->check);
+    }
+    float gm;
+    int t;
+    double S;
+    const bool ok = acquire_row_stats_any(a.records + row * P, (uint64_t)row * (uint64_t)P, P, kWaveSize, lane, true, kLog2eD,
+                                          a.reader_nonce, a.spin_limit, gm, t, S);
+    if (lane != 0) return;
+    bool have_word = (wc == word_check(wv, a.reader_nonce, (uint64_t)b));
+    if (have_word) xwg_store64(&word->check, 0ull);
+    else have_word = acquire_word(word, a.reader_nonce, (uint64_t)b, wv, a.spin_limit);
+    const bool loop_reported = have_word && wv != kSeqWordStalled;
+    if (ok) {
+        a.argmax[row] = t;
+        if (a.row_max) a.row_max[row] = gm;
+        if (a.row_sumexp) a.row_sumexp[row] = (float)S;
+        if (loop_reported && (int)wv == k) a.next_token[b] = t;
+    } else {
+        if (loop_reported) {                         // otherwise the loop's own stall is the one that is counted
+            if ((int)wv == k) a.next_token[b] = -1;
+            if (a.status != nullptr) atomicAdd(&a.status[CSD_STATUS_STALLED], 1u);
+        }
+    }
 }
 
 template <int DT>
@@ -288,12 +354,29 @@ __global__ __launch_bounds__(kStreamWaves *kWaveSize, 4) void verify_step_kernel
     __shared__ BlockCounters counters;
     __shared__ int verdict;
     __shared__ RowPartial wave_out[kStreamWaves];
-    if ((int)blockIdx.x >= a.n_stream_wgs) {
-        step_sequences(a, counters, &verdict);
+    __shared__ StepMergeLds merge;
+    const int g = (int)blockIdx.x;
+    if (g >= a.n_stream_wgs) {                       // the streaming workgroups come first in either order
+        if (g < a.n_stream_wgs + a.n_seq_wgs) step_sequences(a, g - a.n_stream_wgs, counters, merge, &verdict);
+        else step_bonus_rows(a, g - a.n_stream_wgs - a.n_seq_wgs);
         return;
     }
-    const int row = blockIdx.x / nsplit;
-    const int split = share_of_workgroup((int)blockIdx.x - row * nsplit, row, nsplit);
+    int row, place;                                  // this streaming workgroup's row and its place among the row's workgroups
+    if (!a.order.bonus_last) {
+        row = g / nsplit;
+        place = g - row * nsplit;
+    } else if (g < a.order.n_draft_wgs) {            // the rows of the draft positions, sequence by sequence
+        const int r = g / nsplit;
+        place = g - r * nsplit;
+        const int b = r / a.k;
+        row = b * (a.k + 1) + (r - b * a.k);
+    } else {                                         // then the bonus rows
+        const int g2 = g - a.order.n_draft_wgs;
+        const int b = g2 / nsplit;
+        place = g2 - b * nsplit;
+        row = b * (a.k + 1) + a.k;
+    }
+    const int split = share_of_workgroup(place, row, nsplit);
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     if (a.update_here && blockIdx.x == 0 && threadIdx.x == 0) step_control_setup(a.ctrl, step_ready_value(a.nonce));
@@ -316,7 +399,7 @@ StreamPlan make_stream_plan(int rows, int V, int dtype) {
     // at once (four workgroups per compute unit): three or four tiles then bring it under that line, and no
     // second round of workgroups has to be dealt out (256 rows of 9 tiles: 22.4 -> 21.9 microseconds per step).
     const int ntr = p.ntiles_row > 0 ? p.ntiles_row : 1;
-    const int64_t resident = 4 * 256;
+    const int64_t resident = kResidentWorkgroups;
     int tiles_per_group = 2;
     if ((int64_t)rows * ((ntr + 1) / 2) > resident) {
         for (int t = 3; t <= 4; ++t)
@@ -342,8 +425,31 @@ WorkspaceLayout make_workspace_layout(const StreamPlan &p, int B, int k) {
     w.partials_bytes = (size_t)p.rows * (size_t)p.nsplit * sizeof(StepRecord);          // one record per streaming workgroup
     w.log_off = (w.partials_off + w.partials_bytes + 255) & ~(size_t)255;
     w.log_bytes = (size_t)B * (size_t)k * sizeof(uint64_t);
-    w.total = (w.log_off + w.log_bytes + 255) & ~(size_t)255;
+    w.words_off = (w.log_off + w.log_bytes + 255) & ~(size_t)255;
+    w.words_bytes = (size_t)B * sizeof(WordRecord);
+    w.total = (w.words_off + w.words_bytes + 255) & ~(size_t)255;
     return w;
+}
+
+// Which grid order a step takes.  With the bonus rows last, the sequence workgroups (which sit behind every
+// streaming workgroup in either order) find the rows they need complete while the bonus rows are still being
+// streamed, so the loop, the lookups and the barrier start that much earlier, and only one round trip (the bonus
+// rows' records) has to follow the last streaming workgroup.  Measured per step, plain order -> bonus rows last:
+// 64 sequences of 9 fp32 rows 59.2 -> 56.8 microseconds, 256 sequences of 5 bf16 rows 103.2 -> 101.9.  A launch that
+// is resident all at once streams every row at the same time; the order then only adds the hand-over of the
+// accepted length (one more dependent round trip when no updates are applied): such launches keep the plain order.
+// (Sequence workgroups placed earlier in the grid, so that they are resident as soon as the draft positions' rows
+// are complete, finish their loop well before the stream ends but take 64 places from streaming workgroups for 17
+// microseconds, and their atomics land on channels that are busy streaming: measured no gain at any position.)
+static std::atomic<int> g_step_order_override{0};   // test hook: 1 forces the plain order, 2 the bonus-rows-last order
+void set_step_order_override(int v) { g_step_order_override.store(v, std::memory_order_relaxed); }
+StepOrder make_step_order(const StreamPlan &p, int B, int k) {
+    StepOrder o;
+    o.n_draft_wgs = B * k * p.nsplit;
+    const int force = g_step_order_override.load(std::memory_order_relaxed);
+    const bool want = (force == 2) || (force == 0 && (int64_t)p.rows * p.nsplit > kResidentWorkgroups);
+    o.bonus_last = (want && k >= 1 && B >= 1) ? 1 : 0;
+    return o;
 }
 
 hipError_t launch_row_partials(const StreamSource &src, int dtype, int V, const StreamPlan &plan, RowPartial *partials,
@@ -389,8 +495,8 @@ hipError_t launch_shard_draft_logits(const void *logits, int dtype, int64_t row_
 hipError_t launch_verify_step(const StreamSource &src, int dtype, int V, const StreamPlan &plan, const EpilogueArgs &a,
                               hipStream_t stream) {
     if (plan.rows == 0 || a.B == 0) return hipSuccess;
-    const int n_seq_wgs = (a.B + kStepSeqWaves - 1) / kStepSeqWaves;
-    const dim3 grid((unsigned)(a.n_stream_wgs + n_seq_wgs)), block(kStreamWaves * kWaveSize);
+    const int n_tail_wgs = a.order.bonus_last ? a.n_seq_wgs : 0;   // the workgroups that take the bonus rows' statistics
+    const dim3 grid((unsigned)(a.n_stream_wgs + a.n_seq_wgs + n_tail_wgs)), block(kStreamWaves * kWaveSize);
     if (dtype == CSD_DTYPE_F32)
         hipLaunchKernelGGL(verify_step_kernel<CSD_DTYPE_F32>, grid, block, 0, stream, src, V, plan.nsplit, a);
     else

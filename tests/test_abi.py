@@ -70,6 +70,23 @@ def test_launch_plan_of_the_streaming_pass():
         assert csd.csd_verify_workspace_bytes(B, k, V, dt) >= 256 + rows * per_row(rows, V, dt) * 32 + B * k * 8
 
 
+def test_grid_order_of_the_step_by_shape():
+    """Launches of more than 1024 streaming workgroups (more than are resident at once) stream the bonus rows last;
+    smaller ones, and steps without a draft position, keep the plain order (a library hook outside csd.h tells)."""
+    from paper_2604_13634_amd import binding as csd
+    lib = csd.load_library()
+    lib.csd_test_step_order_of.restype = ctypes.c_int
+    lib.csd_test_step_order_of.argtypes = [ctypes.c_int] * 4
+    F32, BF16 = csd.CSD_DTYPE_F32, csd.CSD_DTYPE_BF16
+    assert lib.csd_test_step_order_of(256, 4, 256000, BF16) == 1      # 10240 streaming workgroups
+    assert lib.csd_test_step_order_of(64, 8, 152064, F32) == 1        # 5184
+    assert lib.csd_test_step_order_of(32, 7, 151936, BF16) == 0       # 768
+    assert lib.csd_test_step_order_of(8, 5, 128256, BF16) == 0
+    assert lib.csd_test_step_order_of(1, 4, 32000, F32) == 0
+    assert lib.csd_test_step_order_of(4096, 0, 256000, BF16) == 0     # no draft position: nothing to run early
+    assert lib.csd_test_step_order_of(1, 64, 100, F32) == -1
+
+
 def test_argument_errors_are_synchronous_and_enqueue_nothing():
     """Every call below fails validation on the host, so no pointer is ever dereferenced."""
     from paper_2604_13634_amd import binding as b
