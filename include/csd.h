@@ -131,8 +131,10 @@ size_t csd_verify_workspace_bytes(int B, int k, int V, int dtype);
  *   status      [CSD_STATUS_WORDS] counters, incremented (nullable).
  * A step is ONE kernel launch: workgroups that stream the logits, followed in the same grid by one wave per
  * sequence for the verification logic, which waits for its rows' statistics and then applies the updates
- * (batches of more than 256 sequences use a second launch for the updates).  Waits inside the launch are
- * bounded: see CSD_STATUS_STALLED.
+ * (batches of more than 256 sequences use a second launch for the updates).  A step too large to be resident on
+ * the GPU at once streams the bonus rows last: the loop, which never reads them, then starts before the stream has
+ * ended, and one more wave per sequence takes the bonus row's outputs.  Waits inside the launch are bounded: see
+ * CSD_STATUS_STALLED.
  * Scratch
  *   workspace, workspace_bytes   >= csd_verify_workspace_bytes(B,k,V,dtype), 16-byte aligned; needs no
  *                         initialisation and carries nothing from one call to the next (any content will do).
