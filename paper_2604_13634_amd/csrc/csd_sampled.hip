@@ -462,6 +462,7 @@ __device__ __forceinline__ Divergence sampled_sequence(const SampledArgs &a, int
     out.counted = false;
     out.key = 0;
     out.probe = OcmProbe{0, 0, false, false};
+    out.n = 0;
     stalled = stalled_before;
     if (stalled_before) return out;
     // the draws of this sequence's rows: lane i takes row i's
@@ -564,6 +565,7 @@ __global__ __launch_bounds__(kSegBlockWaves *kWaveSize) void sampled_tail_kernel
     dv.counted = false;
     dv.key = 0;
     dv.probe = OcmProbe{0, 0, false, false};
+    dv.n = 0;
     if (b < a.B) {                                         // wave-uniform: a wave takes a sequence or none
         bool stalled = false, stalled_before = false;
         dv = sampled_sequence(a, b, lane, counters, stalled, stalled_before);

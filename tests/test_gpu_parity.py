@@ -354,6 +354,36 @@ def test_in_kernel_updates_equal_replayed_log_at_full_batch():
     assert torch.equal(bfa.status, bfb.status)
 
 
+@pytest.mark.parametrize("B,k", [(256, 4), (64, 63), (7, 3)])
+def test_every_position_of_a_step_diverges_on_one_pair(B, k):
+    """The most skewed step there is: every draft position of every sequence holds the same (draft, target) pair,
+    with a ratio that passes the gate.  A sequence workgroup sends its equal pairs to the memory as one add of their
+    number (up to 4 x 63 lanes merging in its LDS table), so B*k increments reach one slot from at most B/4 adds.
+    Step 1 counts one divergence per sequence and stops there; once the pair is frequent every position is rescued
+    and counted.  Every step against the oracle, counts included; a second pair on one position checks that the
+    merge keeps pairs apart."""
+    V = 5003
+    rng = np.random.default_rng(B * 64 + k)
+    z = (rng.standard_normal((B, k + 1, V)) * 0.5).astype(np.float32)
+    z[:, :, 11] = 9.0                                   # target token 11 on every row
+    z[:, :k, 7] = 8.5                                   # draft token 7: ratio exp(-0.5) = 0.61 passes tau = 0.3
+    z[0, 0, 13] = 8.8                                   # one position drafts token 13 instead
+    draft = np.full((B, k), 7, dtype=np.int32)
+    draft[0, 0] = 13
+    zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+    ocm = csd.new_ocm(1 << 8)
+    orc = O.CSDOracle()
+    bf = None
+    for step in range(5):
+        bf = csd.csd_verify(zt, dt, 0.3, 2, ocm, buffers=bf)
+        torch.cuda.synchronize()
+        res = orc.verify_step(z, draft, tau=np.float32(0.3), lam=2)
+        compare_step(res, bf, "B=%d k=%d step %d" % (B, k, step))
+        compare_table(ocm, orc, "B=%d k=%d step %d" % (B, k, step))
+    T = decode_ocm(ocm)
+    assert set(T) == {(7, 11), (13, 11)} and T[(7, 11)] > 2 * B * k and bf.accept_len.cpu().tolist() == [k] * B
+
+
 @pytest.mark.parametrize("B", [300, 700, 2200])
 def test_large_batches_update_paths(B):
     """B*k of 1200 and 2800 (several merge batches inside the finish kernel) and 8800 (beyond what the
