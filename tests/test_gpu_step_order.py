@@ -131,3 +131,52 @@ def test_both_orders_agree_on_a_full_size_step():
     for name in ("accept_len", "next_token", "argmax", "pos_flags", "rej_log", "row_max", "row_sumexp", "ratio", "p_draft"):
         assert torch.equal(getattr(b0, name), getattr(b1, name)), name
     assert t0 == t1 and int(b0.status[csd.CSD_STATUS_RESCUED]) > 0
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_in_both_orders(seed):
+    """Random small shapes (batches that are no multiple of four, k from 0 to 12, vocabularies from a handful of
+    tokens to tens of thousands, both storage types, a few ids outside the vocabulary), four steps on the same
+    inputs with a threshold of 1 so that pairs counted in one step are rescued in the next: every step and every
+    memory against the oracle, in the plain order and with the bonus rows last."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 41))
+    k = int(rng.integers(0, 13))
+    V = int(rng.choice([3, 17, 260, 2049, 9001, 33000]))
+    bf16 = bool(rng.integers(0, 2))
+    z = (rng.standard_normal((B, k + 1, V)) * 2).astype(np.float32)
+    top = z.argmax(axis=-1)
+    m = z.max(axis=-1)
+    draft = np.zeros((B, k), dtype=np.int32)
+    for b in range(B):
+        for i in range(k):
+            u = rng.random()
+            if u < 0.5 or V < 4:
+                draft[b, i] = top[b, i]
+            elif u < 0.9:                               # a planted neighbour: ratio 0.61 (passes 0.2) or 0.08 (does not)
+                d = (int(top[b, i]) + 1 + int(rng.integers(0, 2))) % V
+                z[b, i, d] = m[b, i] - (0.5 if u < 0.75 else 2.5)
+                draft[b, i] = d
+            elif u < 0.97:
+                draft[b, i] = int(rng.integers(0, V))
+            else:
+                draft[b, i] = -1 if rng.random() < 0.5 else V + 3
+    if bf16:
+        z = P.f32_to_bf16_bits(z).reshape(B, k + 1, V)
+    zt, dt = to_device_logits(z), torch.from_numpy(draft).cuda()
+    for order in (ORDER_PLAIN, ORDER_BONUS_LAST):
+        _set_order(order)
+        try:
+            ocm = csd.new_ocm(1 << 10)
+            orc = O.CSDOracle()
+            bf = None
+            for step in range(4):
+                bf = csd.csd_verify(zt, dt, 0.2, 1, ocm, buffers=bf)
+                torch.cuda.synchronize()
+                res = orc.verify_step(z, draft, tau=np.float32(0.2), lam=1)
+                what = "seed %d B=%d k=%d V=%d %s order %d step %d" % (seed, B, k, V, "bf16" if bf16 else "f32", order, step)
+                compare_step(res, bf, what)
+                compare_table(ocm, orc, what)
+            assert int(bf.status[csd.CSD_STATUS_STALLED]) == 0
+        finally:
+            _set_order(ORDER_BY_SHAPE)
