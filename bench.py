@@ -419,7 +419,7 @@ def main() -> int:
     ap.add_argument("--ingest-pmc", nargs=2, metavar=("FETCH", "WRITE"))
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU only (there is no multi-GPU path); use --gpus 1", file=sys.stderr)
         return 2
 
     from gen import CONFIGS
