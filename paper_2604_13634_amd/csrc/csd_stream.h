@@ -6,7 +6,7 @@
 // step needs the target distribution's normaliser, the greedy target token t* and, later, single probabilities
 // (Eq. 3 and the p_i(.) of Algorithm 1):
 //     m = max_v z_v,   t* = min{v : z_v == m},   S = sum_v exp(z_v - m).
-// Every logit is read from HBM exactly once with non-temporal 16-byte loads; nothing is reused, so this
+// Every logit is read from HBM exactly once with non-temporal 16-byte loads (buffer loads for bf16); nothing is reused, so this
 // pass is bound by HBM bandwidth (no MFMA, no LDS staging).  A row's 32 KiB tiles are cut into
 // `nsplit` contiguous runs, one per workgroup of 4 waves (dealing the tiles round-robin to the row's workgroups
 // instead measures the same); inside a tile the waves interleave 1 KiB wave-loads.
@@ -34,6 +34,15 @@ constexpr double kLog2eD = (double)CSD_LOG2E_F32;
 constexpr float kRescaleGapLog2 = 28.8f;   // reference stays within this of the maximum, in exponent (log2) units:
                                            // 20 logits at temperature 1; below 32 keeps the exponent's ulp at 2^-19 or finer
 constexpr int kNoIter = 0x7fffffff;
+constexpr int kBufferRsrcFlags = 0x00020000;   // fourth word of a raw buffer descriptor on gfx9: 32-bit data format, no swizzle
+constexpr int kBufferNonTemporal = 2;          // cache-policy bits of a buffer load: the `nt` bit alone
+// Which storage types sweep with buffer loads.  The bf16 sweep keeps the vector ALUs two thirds busy, and the 64-bit
+// address arithmetic of global loads is vector-ALU work: buffer loads took 1.2 - 2 microseconds (1 - 2 %) off the
+// largest bf16 step and put the streaming pass at the rate of a read-only kernel.  (Of the cache-policy bits only
+// `nt` matters: plain, sc0, sc1 or both read 6.2 TB/s in a read-only probe, every combination with nt 6.97.)  The
+// fp32 sweep has the ALUs one third busy and nothing to gain there; its step measured 0.6 microseconds slower with
+// buffer loads (the streaming pass alone 0.35 faster), so it keeps the global loads.
+template <int DT> constexpr bool kBufferLoads = (DT == CSD_DTYPE_BF16);
 constexpr int kRemIter = 1 << 30;      // best_it values at or above this index the remainder loop
 
 // Which share of its row a streaming workgroup takes: the workgroup's place in the row, rotated by the row when
@@ -93,12 +102,22 @@ __device__ __forceinline__ RowPartial stream_row_share(const char *__restrict__ 
     // ---- whole tiles: U independent non-temporal 16-byte loads per lane.
     // Local tile t is row tile tile0 + t; its chunk for (u, this lane) is
     //     (tile0 + t) * kTileChunks + u*WL + lane_chunk0   < ntiles_row * kTileChunks <= nfull.
+    // bf16: buffer loads - one 32-bit offset per lane and the eight loads' strides in the instruction's scalar
+    // offset; the descriptor covers the row's whole chunks, every offset below lies inside it.
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)rowp, 0, nfull * 16, kBufferRsrcFlags);
+    int voff = (tile0 * kTileChunks + lane_chunk0) * 16;
     const u32x4 *p = (const u32x4 *)rowp + (size_t)tile0 * kTileChunks + lane_chunk0;
     for (int t = 0; t < ntiles; ++t) {
         u32x4 q[U];
+        if constexpr (kBufferLoads<DT>) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(p + u * WL);
-        p += kTileChunks;
+            for (int u = 0; u < U; ++u) q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, u * WL * 16, kBufferNonTemporal);
+            voff += kTileChunks * 16;
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(p + u * WL);
+            p += kTileChunks;
+        }
 
         float x[U][E];
 #pragma unroll

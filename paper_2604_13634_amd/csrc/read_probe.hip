@@ -1,5 +1,5 @@
 // Read-only bandwidth probe with the load shape of the streaming pass: workgroups of 4 waves, 8 non-temporal
-// 16-byte loads in flight per lane, a row's 32 KiB tiles cut into `nsplit` contiguous runs, one per workgroup.  It does no
+// 16-byte buffer loads in flight per lane, a row's 32 KiB tiles cut into `nsplit` contiguous runs, one per workgroup.  It does no
 // arithmetic beyond OR-ing the loaded words together (so that the loads cannot be dropped), which makes its
 // rate the ceiling of this access pattern on this machine.  Benchmark support only: it is not part of the
 // verification library and csd.h does not declare it.
@@ -19,15 +19,18 @@ __global__ __launch_bounds__(kWaves *kLanes, 4) void read_probe_kernel(const cha
     const int64_t base_tiles = ntiles_row / nsplit, extra = ntiles_row - base_tiles * nsplit;
     const int64_t tile0 = split * base_tiles + (split < extra ? split : extra);
     const int64_t ntiles = base_tiles + (split < extra ? 1 : 0);
-    const u32x4 *p = (const u32x4 *)(base + (int64_t)row * pitch) + tile0 * kTileChunks + threadIdx.x;
+    // the streaming pass's loads: non-temporal buffer loads, one descriptor per row (its whole tiles), one 32-bit offset per lane
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(base + (int64_t)row * pitch), 0,
+                                                                          (int)(ntiles_row * kTileChunks * 16), 0x00020000);
+    int voff = (int)((tile0 * kTileChunks + threadIdx.x) * 16);
     u32x4 acc = {0u, 0u, 0u, 0u};
     for (int64_t t = 0; t < ntiles; ++t) {
         u32x4 q[kLoads];
 #pragma unroll
-        for (int u = 0; u < kLoads; ++u) q[u] = __builtin_nontemporal_load(p + u * (kWaves * kLanes));
+        for (int u = 0; u < kLoads; ++u) q[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, u * kWaves * kLanes * 16, 2);
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) acc |= q[u];
-        p += kTileChunks;
+        voff += kTileChunks * 16;
     }
     const uint32_t v = acc.x | acc.y | acc.z | acc.w;
     if (v == 0x9E3779B9u) sink[0] = v;                    // practically never: the store only keeps `acc` alive
@@ -42,7 +45,7 @@ extern "C" int64_t csd_probe_read(const void *base, int64_t pitch, int rows, int
         return 0;
     const int64_t chunks = row_bytes / 16;
     const int64_t ntiles = chunks / kTileChunks;
-    if (ntiles == 0 || (int64_t)rows * nsplit > 0x7fffffff) return 0;
+    if (ntiles == 0 || (int64_t)rows * nsplit > 0x7fffffff || row_bytes > 0x7fffffff) return 0;   // 32-bit offsets inside a row
     hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)(rows * nsplit)), dim3(kWaves * kLanes), 0, (hipStream_t)stream,
                        (const char *)base, pitch, chunks, nsplit, (uint32_t *)sink);
     if (hipGetLastError() != hipSuccess) return 0;
