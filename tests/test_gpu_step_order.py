@@ -180,3 +180,25 @@ def test_random_shapes_in_both_orders(seed):
             assert int(bf.status[csd.CSD_STATUS_STALLED]) == 0
         finally:
             _set_order(ORDER_BY_SHAPE)
+
+
+def test_orders_alternate_on_one_workspace():
+    """The same buffers and workspace, the grid order switched from call to call: what one order leaves behind (records,
+    sequence words, the barrier's control head) never passes for the other's; every step against the oracle."""
+    w = Workload(CONFIGS[2], V=6007, B=21)
+    cfg = w.cfg
+    ocm = csd.new_ocm(1 << 12)
+    orc = O.CSDOracle()
+    bf = None
+    try:
+        for step in range(8):
+            _set_order(ORDER_BONUS_LAST if step % 2 else ORDER_PLAIN)
+            z, draft = w.step(step)
+            bf = csd.csd_verify(to_device_logits(z), torch.from_numpy(draft).cuda(), cfg.tau, 1, ocm, buffers=bf)
+            torch.cuda.synchronize()
+            res = orc.verify_step(z, draft, tau=np.float32(cfg.tau), lam=1)
+            compare_step(res, bf, "alternating orders, step %d" % step)
+            compare_table(ocm, orc, "alternating orders, step %d" % step)
+    finally:
+        _set_order(ORDER_BY_SHAPE)
+    assert int(bf.status[csd.CSD_STATUS_STALLED]) == 0 and int(bf.status[csd.CSD_STATUS_RESCUED]) > 0
